@@ -1,0 +1,157 @@
+/*
+ * d2mhe -- MI355X (gfx950) hot path of the private gradient exchange of D2-MHE
+ * (arXiv 2207.04604): multiparty BFV over R_q = Z_q[X]/(X^N+1) in RNS form.
+ *
+ * C ABI.  Every data buffer is CALLER-OWNED DEVICE MEMORY unless a parameter is marked
+ * "host"; the library never allocates or frees device memory.  Its tables live in a
+ * caller-provided device workspace.  All device pointers must be 16-byte aligned.
+ * Calls enqueue work on the given hipStream_t (passed as void*, NULL = default stream)
+ * and do not synchronise, except create / destroy.  No exception or abort crosses the
+ * ABI; every call returns a status (0 = OK, negative = error, see d2mhe_strerror).
+ * A context is immutable after create: concurrent calls on different streams with
+ * disjoint output buffers are legal.
+ *
+ * Notation (Sec. 3.2, Sec. 4.2 of the paper): N ring degree, L RNS limbs q_0..q_{L-1},
+ * Q = prod q_i, t plaintext modulus, Lambda = floor(Q/t), K members of a closed
+ * neighbourhood {i} u N_i ("group"), C ciphertexts per gradient vector.
+ *
+ * Data forms
+ *   coefficient form : uint64 [..][N], natural order, canonical residues.
+ *   evaluation form  : uint64 [..][N]; position p holds xhat[perm[p]], where
+ *                      xhat[j] = sum_n x[n] psi_i^((2j+1) n) mod q_i, psi_i = x^((q_i-1)/2N)
+ *                      for the smallest x >= 2 with psi_i^N = -1, and perm is returned
+ *                      by d2mhe_ntt_index_map.  Canonical residues in [0, q_i).
+ *   d2mhe_ntt_forward / d2mhe_ntt_inverse convert between the two.
+ *
+ *   plaintext        pt    [C][N]        coefficient form, values in [0, t)
+ *   ciphertext       ct    [C][2][L][N]  evaluation form, (c0, c1), limb-major
+ *   decryption share share [C][L][N]     evaluation form
+ *   pk0 share        [L][N]              evaluation form
+ *   prepared key     [2][L][N] words per polynomial: the evaluation-form values [L][N]
+ *                    followed by their Shoup quotients floor(v * 2^64 / q_i) [L][N].
+ *                    sk_share = one prepared polynomial (2*L*N words);
+ *                    pk = two prepared polynomials p0, p1 (4*L*N words).
+ *
+ * Randomness: Philox4x32-10 keyed by `seed`; counter = (block, ciphertext index, party,
+ * domain | limb << 8 | group << 16).  Ternary coefficient n = word n&3 of block n>>2,
+ * value floor(3w/2^32)-1; centred-binomial coefficient n = words 2(n&1), 2(n&1)+1 of block
+ * n>>1, popcount(low eta bits) difference; uniform coefficient n = 128-bit block n mod q_i.
+ * Domains: 1 secret share, 2 public-key error, 3 common random polynomial (per limb),
+ * 4/5/6 mu/e0/e1 of Encrypt, 7 decryption-share error, 8 benchmark polynomials.
+ */
+#ifndef D2MHE_H
+#define D2MHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct d2mhe_ctx d2mhe_ctx; /* opaque, host memory owned by the library */
+typedef int32_t d2mhe_status;
+
+enum {
+    D2MHE_OK = 0,
+    D2MHE_ERR_BAD_PARAMS = -1,    /* N, L, q_i, t, eta outside what is documented below   */
+    D2MHE_ERR_NULL = -2,          /* a required pointer is NULL                            */
+    D2MHE_ERR_ALIGN = -3,         /* a device pointer is not 16-byte aligned               */
+    D2MHE_ERR_RANGE = -4,         /* an index or count is out of range                     */
+    D2MHE_ERR_WORKSPACE = -5,     /* workspace / scratch too small                         */
+    D2MHE_ERR_HIP = -6,           /* a HIP runtime call failed (d2mhe_last_hip_error)      */
+    D2MHE_ERR_UNIMPLEMENTED = -7  /* valid request that this build does not cover          */
+};
+
+typedef struct {
+    uint32_t log2_n;      /* 10..16                                                         */
+    uint32_t num_limbs;   /* L, 1..16                                                       */
+    const uint64_t *q;    /* host: L distinct primes < 2^61, q_i = 1 (mod 2N)               */
+    uint64_t t;           /* prime, t = 1 (mod 2N), t < 2^31, t < min q_i;
+                             0 = transform-only context (no encode/encrypt/decrypt)         */
+    uint32_t cbd_eta;     /* 1..32: error = popcount(eta bits) - popcount(eta bits)          */
+    uint32_t frac_bits;   /* f: fixed-point fraction bits, 0..30                            */
+    uint32_t max_group;   /* K_max >= 1: encode clamps to +-floor(((t-1)/2)/K_max)          */
+    uint64_t seed;        /* Philox key                                                     */
+} d2mhe_params;
+
+/* ---- context ------------------------------------------------------------------------- */
+/* Bytes of device workspace that d2mhe_create needs for these parameters (0 if invalid). */
+size_t d2mhe_workspace_bytes(const d2mhe_params *params);
+/* Validates the parameters, builds twiddle / constant tables on the host, copies them into
+ * `dev_workspace` (synchronously) and derives the common random polynomial p1 of
+ * MBFV.PubKeyGen (Sec. 4.2 item 2).  The workspace must outlive the context.             */
+d2mhe_status d2mhe_create(const d2mhe_params *params, void *dev_workspace, size_t bytes,
+                          void *stream, d2mhe_ctx **out);
+void d2mhe_destroy(d2mhe_ctx *ctx);
+const char *d2mhe_strerror(d2mhe_status status);
+int d2mhe_last_hip_error(const d2mhe_ctx *ctx);
+/* host: perm[p] = index j of the evaluation xhat[j] stored at position p (N entries).    */
+d2mhe_status d2mhe_ntt_index_map(const d2mhe_ctx *ctx, uint32_t *perm_host);
+/* host: psi_i of limb i (i == L: the slot root psi_t), for inspection.                   */
+uint64_t d2mhe_root(const d2mhe_ctx *ctx, uint32_t limb);
+
+/* ---- negacyclic transforms (R_q ring products, Sec. 3.2) -------------------------------- */
+/* polys [B][L][N] in place: coefficient form -> evaluation form and back.                */
+d2mhe_status d2mhe_ntt_forward(d2mhe_ctx *ctx, uint64_t *polys, uint32_t B, void *stream);
+d2mhe_status d2mhe_ntt_inverse(d2mhe_ctx *ctx, uint64_t *polys, uint32_t B, void *stream);
+/* Uniform benchmark polynomials (Philox domain 8), coefficient form, out [B][L][N].      */
+d2mhe_status d2mhe_bench_polys(d2mhe_ctx *ctx, uint64_t *out, uint32_t B, void *stream);
+
+/* ---- set-up: MBFV.SecKeyGen and MBFV.PubKeyGen (Sec. 4.2 items 1, 2) ---------------------- */
+/* Party k: s_k ternary, e_k error; sk_share = prepared s_k (2*L*N words);
+ * pk0_share = -(p1 s_k + e_k) [L][N].                                                     */
+d2mhe_status d2mhe_keygen_share(d2mhe_ctx *ctx, uint32_t party, uint64_t *sk_share,
+                                uint64_t *pk0_share, void *stream);
+/* pk = ([sum_k p0_k]_q, p1) as two prepared polynomials (4*L*N words).
+ * pk0_shares: HOST array of K device pointers.                                            */
+d2mhe_status d2mhe_aggregate_pk(d2mhe_ctx *ctx, const uint64_t *const *pk0_shares, uint32_t K,
+                                uint64_t *pk, void *stream);
+
+/* ---- per round (Alg. 2 lines 6-9) ---------------------------------------------------------- */
+/* Fixed point + slot packing: value c*N+j goes to slot j of plaintext c; r = rint(v 2^f)
+ * (float32, ties to even), NaN -> 0, clamped; pt [C][N]; needs n_values <= C*N, the tail
+ * is zero.                                                                                */
+d2mhe_status d2mhe_encode(d2mhe_ctx *ctx, const float *grad, uint64_t n_values, uint64_t *pt,
+                          uint32_t C, void *stream);
+/* BFV.Encrypt (Sec. 3.2 item 3) under the collective key: ct_c = (Lambda m_c + mu p0 + e0,
+ * mu p1 + e1) for c = 0..C-1, randomness indexed by (party, group, ct_base + c).          */
+d2mhe_status d2mhe_encrypt(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_t *pt, uint32_t C,
+                           uint32_t party, uint32_t group, uint32_t ct_base, uint64_t *ct,
+                           void *stream);
+/* BFV.Add: ct_acc += ct_in (C ciphertexts).                                              */
+d2mhe_status d2mhe_add(d2mhe_ctx *ctx, uint64_t *ct_acc, const uint64_t *ct_in, uint32_t C,
+                       void *stream);
+/* Share of the collective decryption, Eq. (1) without the target-key terms:
+ * h_k = s_k c1 + e_k, randomness indexed by (party, group, ct_base + c).                  */
+d2mhe_status d2mhe_partial_decrypt(d2mhe_ctx *ctx, const uint64_t *sk_share, const uint64_t *ct,
+                                   uint32_t C, uint32_t party, uint32_t group, uint32_t ct_base,
+                                   uint64_t *share, void *stream);
+/* y = c0 + sum_k h_k, pt = [round(t y / Q)]_t (BFV.Decrypt, Sec. 3.2 item 5).  shares: HOST
+ * array of K device pointers, each [C][L][N].  The rounding is exact whenever t*y/Q is
+ * farther than L*2^-62 from a half-integer (always, unless decryption noise overflowed).   */
+d2mhe_status d2mhe_combine(d2mhe_ctx *ctx, const uint64_t *ct, const uint64_t *const *shares,
+                           uint32_t K, uint32_t C, uint64_t *pt, void *stream);
+/* Inverse of d2mhe_encode: slots -> centred representatives -> float32 * 2^-f.           */
+d2mhe_status d2mhe_decode(d2mhe_ctx *ctx, const uint64_t *pt, uint32_t C, uint64_t n_values,
+                          float *out, void *stream);
+
+/* ---- fused round for one group (same results as the calls above) ---------------------------- */
+/* Scratch bytes needed by d2mhe_round_group for K members and n_values gradient entries. */
+size_t d2mhe_round_scratch_bytes(const d2mhe_ctx *ctx, uint32_t K, uint64_t n_values);
+/* Every member encodes + encrypts its gradient under pk, the ciphertexts are summed, every
+ * member produces a decryption share, the shares are combined and decoded into out_sum
+ * [n_values] (the sum of the members' fixed-point gradients).
+ * sk_shares, grads: HOST arrays of K device pointers; members: HOST array of K party ids.
+ * scratch: device memory; after the call it holds, in this order, the K*C fresh
+ * ciphertexts [K][C][2][L][N], the aggregate [C][2][L][N] and the shares [K][C][L][N].    */
+d2mhe_status d2mhe_round_group(d2mhe_ctx *ctx, const uint64_t *pk,
+                               const uint64_t *const *sk_shares, const float *const *grads,
+                               const uint32_t *members, uint32_t K, uint32_t group,
+                               uint64_t n_values, float *out_sum, void *scratch,
+                               size_t scratch_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

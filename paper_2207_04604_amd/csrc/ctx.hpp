@@ -1,0 +1,65 @@
+// Internal declarations shared by the API translation unit and the per-ring-degree
+// kernel instantiations.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "../../include/d2mhe.h"
+#include "kernels.hpp"
+
+struct d2mhe_ctx {
+    uint32_t log2n, L;
+    size_t N;
+    uint64_t q[d2::MAX_LIMBS];
+    uint64_t psi[d2::MAX_LIMBS + 1];
+    uint64_t t;
+    uint32_t max_group;
+    d2::RoundConst rc;
+    const d2::LimbTab *d_tabs;
+    uint64_t *d_p1;     // prepared common random polynomial [2][L][N]
+    int last_hip;
+};
+
+namespace d2 {
+
+inline d2mhe_status hip_fail(d2mhe_ctx *ctx, hipError_t e)
+{
+    if (ctx) ctx->last_hip = (int)e;
+    return D2MHE_ERR_HIP;
+}
+
+#define D2_HIP(ctx, call)                                        \
+    do {                                                         \
+        hipError_t e_ = (call);                                  \
+        if (e_ != hipSuccess) return d2::hip_fail((ctx), e_);    \
+    } while (0)
+
+#define D2_LAUNCHED(ctx) D2_HIP((ctx), hipGetLastError())
+
+// Kernel launchers of one ring degree (one engine shape); defined in inst_<log2n>.hip.
+struct EngineOps {
+    int elog, logb;
+    d2mhe_status (*ntt)(d2mhe_ctx *, uint64_t *polys, uint32_t B, bool forward, hipStream_t);
+    d2mhe_status (*keygen)(d2mhe_ctx *, uint32_t party, uint64_t *sk, uint64_t *pk0, hipStream_t);
+    d2mhe_status (*encode)(d2mhe_ctx *, const float *grad, uint64_t n_values, uint64_t *pt, uint32_t C, hipStream_t);
+    d2mhe_status (*decode)(d2mhe_ctx *, const uint64_t *pt, uint32_t C, uint64_t n_values, float *out, hipStream_t);
+    // from_float: src holds gradients (encoded on the fly), otherwise plaintext polynomials
+    d2mhe_status (*encrypt)(d2mhe_ctx *, bool from_float, const uint64_t *pk, const PtrList &src, const IdList &ids,
+                            uint32_t members, uint32_t group, uint32_t ct_base, uint64_t n_values, uint64_t *ct,
+                            uint32_t C, hipStream_t);
+    d2mhe_status (*share)(d2mhe_ctx *, const PtrList &sks, const IdList &ids, uint32_t members, uint32_t group,
+                          uint32_t ct_base, const uint64_t *ct, uint64_t *shares, size_t share_stride, uint32_t C,
+                          hipStream_t);
+    // out != nullptr: decode to floats; otherwise store the plaintext polynomials in pt
+    d2mhe_status (*combine)(d2mhe_ctx *, const uint64_t *ct, const PtrList &shares, uint32_t K, uint32_t C,
+                            uint64_t *pt, float *out, uint64_t n_values, hipStream_t);
+};
+
+const EngineOps *ops_10();
+const EngineOps *ops_11();
+const EngineOps *ops_12();
+const EngineOps *ops_13();
+const EngineOps *ops_14();
+const EngineOps *ops_15();
+const EngineOps *ops_16();
+
+}  // namespace d2

@@ -1,0 +1,518 @@
+// C-ABI entry points of the d2mhe library (see include/d2mhe.h): parameter validation,
+// host-side table construction and kernel launches.  No device memory is allocated here.
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "ctx.hpp"
+#include "stream_kernels.hpp"
+
+using namespace d2;
+
+namespace {
+
+typedef unsigned __int128 u128;
+
+// ---- host number theory (set-up only) -------------------------------------------------
+uint64_t h_mul(uint64_t a, uint64_t b, uint64_t m) { return (uint64_t)((u128)a * b % m); }
+
+uint64_t h_pow(uint64_t base, uint64_t exp, uint64_t m)
+{
+    uint64_t acc = 1 % m;
+    for (base %= m; exp; exp >>= 1, base = h_mul(base, base, m))
+        if (exp & 1) acc = h_mul(acc, base, m);
+    return acc;
+}
+
+uint64_t h_inv(uint64_t a, uint64_t prime) { return h_pow(a, prime - 2, prime); }
+
+// Miller-Rabin with the first twelve primes as witnesses: deterministic below 2^64.
+bool h_is_prime(uint64_t n)
+{
+    const uint64_t wit[] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37};
+    if (n < 2) return false;
+    for (uint64_t p : wit) {
+        if (n == p) return true;
+        if (n % p == 0) return false;
+    }
+    int twos = 0;
+    uint64_t odd = n - 1;
+    while (!(odd & 1)) { odd >>= 1; ++twos; }
+    for (uint64_t a : wit) {
+        uint64_t y = h_pow(a, odd, n);
+        if (y == 1 || y == n - 1) continue;
+        bool composite = true;
+        for (int i = 1; i < twos && composite; ++i) {
+            y = h_mul(y, y, n);
+            if (y == n - 1) composite = false;
+        }
+        if (composite) return false;
+    }
+    return true;
+}
+
+// psi = x^((m-1)/2N) for the smallest x >= 2 such that psi has order exactly 2N.
+uint64_t h_root(uint64_t m, uint32_t log2n)
+{
+    const uint64_t n = 1ull << log2n, e = (m - 1) / (2 * n);
+    for (uint64_t x = 2; x < m; ++x) {
+        uint64_t psi = h_pow(x, e, m);
+        if (h_pow(psi, n, m) == m - 1) return psi;
+    }
+    return 0;
+}
+
+uint64_t h_shoup(uint64_t w, uint64_t m) { return (uint64_t)(((u128)w << 64) / m); }
+
+Tw h_tw(uint64_t w, uint64_t m)
+{
+    Tw t;
+    t.w = w;
+    t.ws = h_shoup(w, m);
+    return t;
+}
+
+uint32_t h_bitrev(uint32_t v, int bits)
+{
+    uint32_t r = 0;
+    for (int i = 0; i < bits; ++i) r |= ((v >> i) & 1u) << (bits - 1 - i);
+    return r;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- engine shape per ring degree ----------------------------------------------------------
+const EngineOps *engine_ops(uint32_t log2n)
+{
+    switch (log2n) {
+    case 10: return ops_10();
+    case 11: return ops_11();
+    case 12: return ops_12();
+    case 13: return ops_13();
+    case 14: return ops_14();
+    case 15: return ops_15();
+    case 16: return ops_16();
+    default: return nullptr;
+    }
+}
+
+struct Layout {
+    size_t tabs_off, tw_off, p1_off, total;
+};
+
+Layout layout_of(uint32_t log2n, uint32_t L, bool has_t)
+{
+    const size_t N = (size_t)1 << log2n;
+    const uint32_t moduli = L + (has_t ? 1 : 0);
+    Layout lo;
+    lo.tabs_off = 0;
+    lo.tw_off = align_up(sizeof(LimbTab) * (MAX_LIMBS + 1), 256);
+    lo.p1_off = lo.tw_off + (size_t)moduli * 2 * N * sizeof(Tw);
+    lo.total = lo.p1_off + (has_t ? (size_t)2 * L * N * sizeof(uint64_t) : 0);
+    return lo;
+}
+
+bool params_ok(const d2mhe_params *p)
+{
+    if (!p || !p->q) return false;
+    if (p->log2_n < 10 || p->log2_n > 16) return false;
+    if (p->num_limbs < 1 || p->num_limbs > (uint32_t)MAX_LIMBS) return false;
+    const uint64_t two_n = 2ull << p->log2_n;
+    for (uint32_t i = 0; i < p->num_limbs; ++i) {
+        const uint64_t q = p->q[i];
+        if (q >> 61) return false;
+        if (q % two_n != 1 || !h_is_prime(q)) return false;
+        for (uint32_t j = 0; j < i; ++j)
+            if (p->q[j] == q) return false;
+    }
+    if (p->t) {
+        if (p->t >> 31) return false;
+        if (p->t % two_n != 1 || !h_is_prime(p->t)) return false;
+        for (uint32_t i = 0; i < p->num_limbs; ++i)
+            if (p->t >= p->q[i]) return false;
+        if (p->cbd_eta < 1 || p->cbd_eta > 32) return false;
+        if (p->frac_bits > 30 || p->max_group < 1) return false;
+    }
+    return true;
+}
+
+}  // namespace
+
+namespace {
+
+bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
+d2mhe_status launch_ntt(d2mhe_ctx *ctx, uint64_t *polys, uint32_t B, bool forward, hipStream_t st)
+{
+    return engine_ops(ctx->log2n)->ntt(ctx, polys, B, forward, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *d2mhe_strerror(d2mhe_status s)
+{
+    switch (s) {
+    case D2MHE_OK: return "ok";
+    case D2MHE_ERR_BAD_PARAMS: return "invalid parameters";
+    case D2MHE_ERR_NULL: return "null pointer";
+    case D2MHE_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    case D2MHE_ERR_RANGE: return "index or count out of range";
+    case D2MHE_ERR_WORKSPACE: return "workspace or scratch too small";
+    case D2MHE_ERR_HIP: return "HIP runtime error";
+    case D2MHE_ERR_UNIMPLEMENTED: return "not implemented for these parameters";
+    default: return "unknown status";
+    }
+}
+
+size_t d2mhe_workspace_bytes(const d2mhe_params *p)
+{
+    if (!params_ok(p)) return 0;
+    return layout_of(p->log2_n, p->num_limbs, p->t != 0).total;
+}
+
+d2mhe_status d2mhe_create(const d2mhe_params *p, void *dev_workspace, size_t bytes, void *stream,
+                          d2mhe_ctx **out)
+{
+    if (!p || !out) return D2MHE_ERR_NULL;
+    *out = nullptr;
+    if (!p->q) return D2MHE_ERR_NULL;
+    if (!params_ok(p)) return D2MHE_ERR_BAD_PARAMS;
+    if (!dev_workspace) return D2MHE_ERR_NULL;
+    if (misaligned(dev_workspace)) return D2MHE_ERR_ALIGN;
+    const uint32_t L = p->num_limbs, log2n = p->log2_n;
+    const size_t N = (size_t)1 << log2n;
+    const bool has_t = p->t != 0;
+    const Layout lo = layout_of(log2n, L, has_t);
+    if (bytes < lo.total) return D2MHE_ERR_WORKSPACE;
+
+    d2mhe_ctx *ctx = new (std::nothrow) d2mhe_ctx();
+    if (!ctx) return D2MHE_ERR_HIP;
+    ctx->log2n = log2n;
+    ctx->L = L;
+    ctx->N = N;
+    ctx->t = p->t;
+    ctx->max_group = p->max_group;
+    ctx->last_hip = 0;
+    char *ws = (char *)dev_workspace;
+    ctx->d_tabs = (const LimbTab *)(ws + lo.tabs_off);
+    ctx->d_p1 = has_t ? (uint64_t *)(ws + lo.p1_off) : nullptr;
+
+    const uint32_t moduli = L + (has_t ? 1 : 0);
+    std::vector<LimbTab> tabs(MAX_LIMBS + 1);
+    std::memset(tabs.data(), 0, sizeof(LimbTab) * tabs.size());
+    std::vector<Tw> tw((size_t)moduli * 2 * N);
+    std::vector<uint64_t> pw(N);
+    uint64_t q_mod_t = 1;
+    for (uint32_t i = 0; has_t && i < L; ++i) q_mod_t = h_mul(q_mod_t, p->q[i] % p->t, p->t);
+    for (uint32_t i = 0; i < moduli; ++i) {
+        // slot L of the table array is the plaintext modulus
+        const uint64_t m = i < L ? p->q[i] : p->t;
+        const uint64_t psi = h_root(m, log2n);
+        if (i < L) ctx->q[i] = m;
+        ctx->psi[i < L ? i : L] = psi;
+        Tw *fwd = tw.data() + (size_t)i * 2 * N, *inv = fwd + N;
+        pw[0] = 1;
+        for (size_t k = 1; k < N; ++k) pw[k] = h_mul(pw[k - 1], psi, m);
+        for (size_t k = 0; k < N; ++k) fwd[k] = h_tw(pw[h_bitrev((uint32_t)k, (int)log2n)], m);
+        const uint64_t psi_inv = h_inv(psi, m);
+        for (size_t k = 1; k < N; ++k) pw[k] = h_mul(pw[k - 1], psi_inv, m);
+        for (size_t k = 0; k < N; ++k) inv[k] = h_tw(pw[h_bitrev((uint32_t)k, (int)log2n)], m);
+        LimbTab &tb = tabs[i < L ? i : L];
+        tb.q = m;
+        const uint64_t ninv = h_inv((uint64_t)N % m, m);
+        tb.ninv = h_tw(ninv, m);
+        tb.wn = h_tw(h_mul(inv[1].w, ninv, m), m);
+        tb.fwd = (const Tw *)(ws + lo.tw_off) + (size_t)i * 2 * N;
+        tb.inv = tb.fwd + N;
+        if (i < L && has_t) {
+            // floor(Q/t) = (Q - (Q mod t)) / t  and  Q = 0 (mod q_i)  =>  floor(Q/t) = -(Q mod t) t^-1 (mod q_i)
+            const uint64_t lam = h_mul((m - q_mod_t % m) % m, h_inv(p->t % m, m), m);
+            tb.lambda = h_tw(lam, m);
+            uint64_t others = 1;
+            for (uint32_t j = 0; j < L; ++j)
+                if (j != i) others = h_mul(others, p->q[j] % m, m);
+            tb.gamma = h_tw(h_inv(others, m), m);
+            const u128 num = (u128)p->t << 64;
+            tb.theta_hi = (uint64_t)(num / m);
+            tb.theta_lo = (uint64_t)(((num % m) << 64) / m);
+        }
+    }
+    if (has_t && L < (uint32_t)MAX_LIMBS) { /* slot L already filled above */ }
+
+    std::memset(&ctx->rc, 0, sizeof(ctx->rc));
+    ctx->rc.t = p->t;
+    ctx->rc.L = L;
+    ctx->rc.key.k0 = (uint32_t)(p->seed & 0xffffffffu);
+    ctx->rc.key.k1 = (uint32_t)(p->seed >> 32);
+    if (has_t) {
+        ctx->rc.eta_mask = p->cbd_eta >= 32 ? 0xffffffffu : ((1u << p->cbd_eta) - 1u);
+        ctx->rc.clamp = (int32_t)(((p->t - 1) / 2) / p->max_group);
+        ctx->rc.scale = (float)(1u << p->frac_bits);
+        ctx->rc.inv_scale = 1.0f / (float)(1u << p->frac_bits);
+    }
+
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = hipMemcpy(ws + lo.tabs_off, tabs.data(), sizeof(LimbTab) * tabs.size(), hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = hipMemcpy(ws + lo.tw_off, tw.data(), tw.size() * sizeof(Tw), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        delete ctx;
+        return D2MHE_ERR_HIP;
+    }
+    if (has_t) {
+        // common random polynomial p1: uniform per limb, to evaluation form, with Shoup quotients
+        const size_t total = (size_t)L * N;
+        hipLaunchKernelGGL(k_uniform, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, ctx->d_p1,
+                           ctx->d_tabs, L, log2n, (uint32_t)DOM_CRS, ctx->rc.key, total);
+        d2mhe_status s = launch_ntt(ctx, ctx->d_p1, 1, true, st);
+        if (s == D2MHE_OK) {
+            PtrList src;
+            src.p[0] = ctx->d_p1;
+            hipLaunchKernelGGL(k_prepare, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, ctx->d_p1, src,
+                               1u, ctx->d_tabs, log2n, total);
+            if (hipGetLastError() != hipSuccess) s = D2MHE_ERR_HIP;
+        }
+        if (s == D2MHE_OK && hipStreamSynchronize(st) != hipSuccess) s = D2MHE_ERR_HIP;
+        if (s != D2MHE_OK) {
+            delete ctx;
+            return s;
+        }
+    }
+    *out = ctx;
+    return D2MHE_OK;
+}
+
+void d2mhe_destroy(d2mhe_ctx *ctx) { delete ctx; }
+
+int d2mhe_last_hip_error(const d2mhe_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+uint64_t d2mhe_root(const d2mhe_ctx *ctx, uint32_t limb)
+{
+    if (!ctx || limb > ctx->L || (limb == ctx->L && !ctx->t)) return 0;
+    return ctx->psi[limb];
+}
+
+d2mhe_status d2mhe_ntt_index_map(const d2mhe_ctx *ctx, uint32_t *perm)
+{
+    if (!ctx || !perm) return D2MHE_ERR_NULL;
+    const EngineOps *ops = engine_ops(ctx->log2n);
+    const int elog = ops->elog, logb = ops->logb;
+    const uint32_t T = 1u << (logb - elog), NB = 1u << logb;
+    for (uint32_t pos = 0; pos < ctx->N; ++pos) {
+        const uint32_t blk = pos >> logb, lp = pos & (NB - 1);
+        const uint32_t idx = (blk << logb) | ((lp % T) << elog) | (lp / T);
+        perm[pos] = h_bitrev(idx, (int)ctx->log2n);
+    }
+    return D2MHE_OK;
+}
+
+d2mhe_status d2mhe_ntt_forward(d2mhe_ctx *ctx, uint64_t *polys, uint32_t B, void *stream)
+{
+    if (!ctx || !polys) return D2MHE_ERR_NULL;
+    if (misaligned(polys)) return D2MHE_ERR_ALIGN;
+    if (B == 0) return D2MHE_OK;
+    if ((uint64_t)B * ctx->L > 65535u && ctx->log2n > 14) return D2MHE_ERR_RANGE;
+    return launch_ntt(ctx, polys, B, true, (hipStream_t)stream);
+}
+
+d2mhe_status d2mhe_ntt_inverse(d2mhe_ctx *ctx, uint64_t *polys, uint32_t B, void *stream)
+{
+    if (!ctx || !polys) return D2MHE_ERR_NULL;
+    if (misaligned(polys)) return D2MHE_ERR_ALIGN;
+    if (B == 0) return D2MHE_OK;
+    if ((uint64_t)B * ctx->L > 65535u && ctx->log2n > 14) return D2MHE_ERR_RANGE;
+    return launch_ntt(ctx, polys, B, false, (hipStream_t)stream);
+}
+
+d2mhe_status d2mhe_bench_polys(d2mhe_ctx *ctx, uint64_t *out, uint32_t B, void *stream)
+{
+    if (!ctx || !out) return D2MHE_ERR_NULL;
+    if (misaligned(out)) return D2MHE_ERR_ALIGN;
+    if (B == 0) return D2MHE_OK;
+    const size_t total = (size_t)B * ctx->L * ctx->N;
+    hipLaunchKernelGGL(k_uniform, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream, out,
+                       ctx->d_tabs, ctx->L, ctx->log2n, (uint32_t)DOM_BENCH, ctx->rc.key, total);
+    D2_LAUNCHED(ctx);
+    return D2MHE_OK;
+}
+
+#define D2_NEED_SCHEME(ctx)                                          \
+    do {                                                             \
+        if (!(ctx)) return D2MHE_ERR_NULL;                           \
+        if (!(ctx)->t) return D2MHE_ERR_BAD_PARAMS;                  \
+        if ((ctx)->log2n > 14) return D2MHE_ERR_UNIMPLEMENTED;       \
+    } while (0)
+
+d2mhe_status d2mhe_keygen_share(d2mhe_ctx *ctx, uint32_t party, uint64_t *sk_share, uint64_t *pk0_share,
+                                void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!sk_share || !pk0_share) return D2MHE_ERR_NULL;
+    if (misaligned(sk_share) || misaligned(pk0_share)) return D2MHE_ERR_ALIGN;
+    if (party > 0xffffu) return D2MHE_ERR_RANGE;
+    return engine_ops(ctx->log2n)->keygen(ctx, party, sk_share, pk0_share, (hipStream_t)stream);
+}
+
+d2mhe_status d2mhe_aggregate_pk(d2mhe_ctx *ctx, const uint64_t *const *pk0_shares, uint32_t K, uint64_t *pk,
+                                void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!pk0_shares || !pk) return D2MHE_ERR_NULL;
+    if (K == 0 || K > (uint32_t)MAX_GROUP || K > ctx->max_group) return D2MHE_ERR_RANGE;
+    if (misaligned(pk)) return D2MHE_ERR_ALIGN;
+    PtrList src;
+    for (uint32_t k = 0; k < K; ++k) {
+        if (!pk0_shares[k]) return D2MHE_ERR_NULL;
+        if (misaligned(pk0_shares[k])) return D2MHE_ERR_ALIGN;
+        src.p[k] = pk0_shares[k];
+    }
+    const size_t total = (size_t)ctx->L * ctx->N;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(k_prepare, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, pk, src, K, ctx->d_tabs,
+                       ctx->log2n, total);
+    D2_LAUNCHED(ctx);
+    D2_HIP(ctx, hipMemcpyAsync(pk + 2 * total, ctx->d_p1, 2 * total * sizeof(uint64_t), hipMemcpyDeviceToDevice, st));
+    return D2MHE_OK;
+}
+
+d2mhe_status d2mhe_encode(d2mhe_ctx *ctx, const float *grad, uint64_t n_values, uint64_t *pt, uint32_t C,
+                          void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!pt || (!grad && n_values)) return D2MHE_ERR_NULL;
+    if (misaligned(pt) || misaligned(grad)) return D2MHE_ERR_ALIGN;
+    if (n_values > (uint64_t)C * ctx->N) return D2MHE_ERR_RANGE;
+    if (C == 0) return D2MHE_OK;
+    return engine_ops(ctx->log2n)->encode(ctx, grad, n_values, pt, C, (hipStream_t)stream);
+}
+
+d2mhe_status d2mhe_decode(d2mhe_ctx *ctx, const uint64_t *pt, uint32_t C, uint64_t n_values, float *out,
+                          void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!pt || (!out && n_values)) return D2MHE_ERR_NULL;
+    if (misaligned(pt) || misaligned(out)) return D2MHE_ERR_ALIGN;
+    if (n_values > (uint64_t)C * ctx->N) return D2MHE_ERR_RANGE;
+    if (C == 0) return D2MHE_OK;
+    return engine_ops(ctx->log2n)->decode(ctx, pt, C, n_values, out, (hipStream_t)stream);
+}
+
+d2mhe_status d2mhe_encrypt(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_t *pt, uint32_t C, uint32_t party,
+                           uint32_t group, uint32_t ct_base, uint64_t *ct, void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!pk || !pt || !ct) return D2MHE_ERR_NULL;
+    if (misaligned(pk) || misaligned(pt) || misaligned(ct)) return D2MHE_ERR_ALIGN;
+    if (party > 0xffffu || group > 0xffffu || (uint64_t)ct_base + C > 0xffffffffull) return D2MHE_ERR_RANGE;
+    if (C == 0) return D2MHE_OK;
+    PtrList src;
+    IdList ids;
+    src.p[0] = pt;
+    ids.v[0] = party;
+    return engine_ops(ctx->log2n)->encrypt(ctx, false, pk, src, ids, 1, group, ct_base, 0, ct, C, (hipStream_t)stream);
+}
+
+d2mhe_status d2mhe_add(d2mhe_ctx *ctx, uint64_t *ct_acc, const uint64_t *ct_in, uint32_t C, void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!ct_acc || !ct_in) return D2MHE_ERR_NULL;
+    if (misaligned(ct_acc) || misaligned(ct_in)) return D2MHE_ERR_ALIGN;
+    if (C == 0) return D2MHE_OK;
+    PtrList src;
+    src.p[0] = ct_acc;
+    src.p[1] = ct_in;
+    const size_t total = (size_t)C * 2 * ctx->L * ctx->N;
+    hipLaunchKernelGGL(k_sum, dim3((unsigned)((total / 2 + 255) / 256)), dim3(256), 0, (hipStream_t)stream, ct_acc,
+                       src, 2u, ctx->d_tabs, ctx->L, ctx->log2n, total);
+    D2_LAUNCHED(ctx);
+    return D2MHE_OK;
+}
+
+d2mhe_status d2mhe_partial_decrypt(d2mhe_ctx *ctx, const uint64_t *sk_share, const uint64_t *ct, uint32_t C,
+                                   uint32_t party, uint32_t group, uint32_t ct_base, uint64_t *share, void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!sk_share || !ct || !share) return D2MHE_ERR_NULL;
+    if (misaligned(sk_share) || misaligned(ct) || misaligned(share)) return D2MHE_ERR_ALIGN;
+    if (party > 0xffffu || group > 0xffffu || (uint64_t)ct_base + C > 0xffffffffull) return D2MHE_ERR_RANGE;
+    if (C == 0) return D2MHE_OK;
+    PtrList sks;
+    IdList ids;
+    sks.p[0] = sk_share;
+    ids.v[0] = party;
+    return engine_ops(ctx->log2n)->share(ctx, sks, ids, 1, group, ct_base, ct, share, 0, C, (hipStream_t)stream);
+}
+
+d2mhe_status d2mhe_combine(d2mhe_ctx *ctx, const uint64_t *ct, const uint64_t *const *shares, uint32_t K, uint32_t C,
+                           uint64_t *pt, void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!ct || !shares || !pt) return D2MHE_ERR_NULL;
+    if (K == 0 || K > (uint32_t)MAX_GROUP || K > ctx->max_group) return D2MHE_ERR_RANGE;
+    if (misaligned(ct) || misaligned(pt)) return D2MHE_ERR_ALIGN;
+    PtrList sh;
+    for (uint32_t k = 0; k < K; ++k) {
+        if (!shares[k]) return D2MHE_ERR_NULL;
+        if (misaligned(shares[k])) return D2MHE_ERR_ALIGN;
+        sh.p[k] = shares[k];
+    }
+    if (C == 0) return D2MHE_OK;
+    return engine_ops(ctx->log2n)->combine(ctx, ct, sh, K, C, pt, nullptr, 0, (hipStream_t)stream);
+}
+
+size_t d2mhe_round_scratch_bytes(const d2mhe_ctx *ctx, uint32_t K, uint64_t n_values)
+{
+    if (!ctx || !ctx->t || K == 0) return 0;
+    const uint64_t C = (n_values + ctx->N - 1) / ctx->N;
+    const size_t LN = (size_t)ctx->L * ctx->N * sizeof(uint64_t);
+    // K*C fresh ciphertexts, one aggregate per index, K*C shares
+    return (size_t)C * ((size_t)K * 2 * LN + 2 * LN + (size_t)K * LN);
+}
+
+d2mhe_status d2mhe_round_group(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_t *const *sk_shares,
+                               const float *const *grads, const uint32_t *members, uint32_t K, uint32_t group,
+                               uint64_t n_values, float *out_sum, void *scratch, size_t scratch_bytes, void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!pk || !sk_shares || !grads || !members || !out_sum || !scratch) return D2MHE_ERR_NULL;
+    if (K == 0 || K > (uint32_t)MAX_GROUP || K > ctx->max_group || group > 0xffffu) return D2MHE_ERR_RANGE;
+    if (n_values == 0) return D2MHE_OK;
+    const uint64_t C64 = (n_values + ctx->N - 1) / ctx->N;
+    if (C64 > 0x7fffffffull) return D2MHE_ERR_RANGE;
+    if (scratch_bytes < d2mhe_round_scratch_bytes(ctx, K, n_values)) return D2MHE_ERR_WORKSPACE;
+    if (misaligned(pk) || misaligned(out_sum) || misaligned(scratch)) return D2MHE_ERR_ALIGN;
+    const uint32_t C = (uint32_t)C64;
+    PtrList gl, sl, cl;
+    IdList ids;
+    const size_t LN = (size_t)ctx->L * ctx->N;
+    uint64_t *cts = (uint64_t *)scratch;
+    uint64_t *agg = cts + (size_t)K * C * 2 * LN;
+    uint64_t *shares = agg + (size_t)C * 2 * LN;
+    for (uint32_t k = 0; k < K; ++k) {
+        if (!sk_shares[k] || !grads[k]) return D2MHE_ERR_NULL;
+        if (misaligned(sk_shares[k]) || misaligned(grads[k])) return D2MHE_ERR_ALIGN;
+        if (members[k] > 0xffffu) return D2MHE_ERR_RANGE;
+        gl.p[k] = grads[k];
+        sl.p[k] = sk_shares[k];
+        cl.p[k] = cts + (size_t)k * C * 2 * LN;
+        ids.v[k] = members[k];
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const EngineOps *ops = engine_ops(ctx->log2n);
+    d2mhe_status s = ops->encrypt(ctx, true, pk, gl, ids, K, group, 0, n_values, cts, C, st);
+    if (s != D2MHE_OK) return s;
+    const size_t total = (size_t)C * 2 * LN;
+    hipLaunchKernelGGL(k_sum, dim3((unsigned)((total / 2 + 255) / 256)), dim3(256), 0, st, agg, cl, K, ctx->d_tabs,
+                       ctx->L, ctx->log2n, total);
+    D2_LAUNCHED(ctx);
+    s = ops->share(ctx, sl, ids, K, group, 0, agg, shares, (size_t)C * LN, C, st);
+    if (s != D2MHE_OK) return s;
+    PtrList hl;
+    for (uint32_t k = 0; k < K; ++k) hl.p[k] = shares + (size_t)k * C * LN;
+    return ops->combine(ctx, agg, hl, K, C, nullptr, out_sum, n_values, st);
+}
+
+}  // extern "C"

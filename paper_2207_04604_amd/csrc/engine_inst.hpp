@@ -1,0 +1,109 @@
+// Launchers for one engine shape; included by inst_<log2n>.hip, which instantiates them.
+#pragma once
+#include "ctx.hpp"
+
+namespace d2 {
+
+template <class ENG>
+struct Launch {
+    static d2mhe_status ntt(d2mhe_ctx *ctx, uint64_t *polys, uint32_t B, bool forward, hipStream_t st)
+    {
+        const uint32_t L = ctx->L, polys_n = B * L;
+        if constexpr (ENG::LOGB == ENG::LOGN) {
+            if (forward)
+                hipLaunchKernelGGL(k_ntt_forward<ENG>, dim3(polys_n), dim3(ENG::T), 0, st, polys, ctx->d_tabs, L);
+            else
+                hipLaunchKernelGGL(k_ntt_inverse<ENG>, dim3(polys_n), dim3(ENG::T), 0, st, polys, ctx->d_tabs, L);
+            D2_LAUNCHED(ctx);
+        } else {
+            // head: top stages across blocks; tail: one workgroup per block
+            constexpr int LOGN = ENG::LOGN, LOGH = LOGN - ENG::LOGB;
+            dim3 hgrid((1u << (LOGN - LOGH)) / 256, polys_n), tgrid(1u << LOGH, polys_n);
+            if (forward) {
+                hipLaunchKernelGGL((k_head_forward<LOGN, LOGH>), hgrid, dim3(256), 0, st, polys, ctx->d_tabs, L);
+                D2_LAUNCHED(ctx);
+                hipLaunchKernelGGL(k_tail_forward<ENG>, tgrid, dim3(ENG::T), 0, st, polys, ctx->d_tabs, L);
+            } else {
+                hipLaunchKernelGGL(k_tail_inverse<ENG>, tgrid, dim3(ENG::T), 0, st, polys, ctx->d_tabs, L);
+                D2_LAUNCHED(ctx);
+                hipLaunchKernelGGL((k_head_inverse<LOGN, LOGH>), hgrid, dim3(256), 0, st, polys, ctx->d_tabs, L);
+            }
+            D2_LAUNCHED(ctx);
+        }
+        return D2MHE_OK;
+    }
+
+    static d2mhe_status keygen(d2mhe_ctx *ctx, uint32_t party, uint64_t *sk, uint64_t *pk0, hipStream_t st)
+    {
+        hipLaunchKernelGGL(k_keygen<ENG>, dim3(ctx->L), dim3(ENG::T), 0, st, party, sk, pk0,
+                           (const uint64_t *)ctx->d_p1, ctx->d_tabs, ctx->rc);
+        D2_LAUNCHED(ctx);
+        return D2MHE_OK;
+    }
+
+    static d2mhe_status encode(d2mhe_ctx *ctx, const float *grad, uint64_t n_values, uint64_t *pt, uint32_t C,
+                               hipStream_t st)
+    {
+        hipLaunchKernelGGL(k_encode<ENG>, dim3(C), dim3(ENG::T), 0, st, grad, n_values, pt, ctx->d_tabs, ctx->rc);
+        D2_LAUNCHED(ctx);
+        return D2MHE_OK;
+    }
+
+    static d2mhe_status decode(d2mhe_ctx *ctx, const uint64_t *pt, uint32_t C, uint64_t n_values, float *out,
+                               hipStream_t st)
+    {
+        hipLaunchKernelGGL(k_decode<ENG>, dim3(C), dim3(ENG::T), 0, st, pt, n_values, out, ctx->d_tabs, ctx->rc);
+        D2_LAUNCHED(ctx);
+        return D2MHE_OK;
+    }
+
+    static d2mhe_status encrypt(d2mhe_ctx *ctx, bool from_float, const uint64_t *pk, const PtrList &src,
+                                const IdList &ids, uint32_t members, uint32_t group, uint32_t ct_base,
+                                uint64_t n_values, uint64_t *ct, uint32_t C, hipStream_t st)
+    {
+        if (from_float)
+            hipLaunchKernelGGL((k_encrypt<ENG, true>), dim3(C, members), dim3(ENG::T), 0, st, pk, src, ids, group,
+                               ct_base, n_values, ct, C, ctx->d_tabs, ctx->rc);
+        else
+            hipLaunchKernelGGL((k_encrypt<ENG, false>), dim3(C, members), dim3(ENG::T), 0, st, pk, src, ids, group,
+                               ct_base, n_values, ct, C, ctx->d_tabs, ctx->rc);
+        D2_LAUNCHED(ctx);
+        return D2MHE_OK;
+    }
+
+    static d2mhe_status share(d2mhe_ctx *ctx, const PtrList &sks, const IdList &ids, uint32_t members, uint32_t group,
+                              uint32_t ct_base, const uint64_t *ct, uint64_t *shares, size_t share_stride, uint32_t C,
+                              hipStream_t st)
+    {
+        hipLaunchKernelGGL(k_share<ENG>, dim3(C, members), dim3(ENG::T), 0, st, sks, ids, group, ct_base, ct, shares,
+                           share_stride, ctx->d_tabs, ctx->rc);
+        D2_LAUNCHED(ctx);
+        return D2MHE_OK;
+    }
+
+    static d2mhe_status combine(d2mhe_ctx *ctx, const uint64_t *ct, const PtrList &shares, uint32_t K, uint32_t C,
+                                uint64_t *pt, float *out, uint64_t n_values, hipStream_t st)
+    {
+        if (out)
+            hipLaunchKernelGGL((k_combine<ENG, true>), dim3(C), dim3(ENG::T), 0, st, ct, shares, K, pt, out, n_values,
+                               ctx->d_tabs, ctx->rc);
+        else
+            hipLaunchKernelGGL((k_combine<ENG, false>), dim3(C), dim3(ENG::T), 0, st, ct, shares, K, pt, out,
+                               n_values, ctx->d_tabs, ctx->rc);
+        D2_LAUNCHED(ctx);
+        return D2MHE_OK;
+    }
+
+    // full set (ring degrees a single workgroup can hold)
+    static EngineOps full()
+    {
+        return EngineOps{ENG::ELOG, ENG::LOGB, &ntt, &keygen, &encode, &decode, &encrypt, &share, &combine};
+    }
+    // transforms only (longer rings)
+    static EngineOps transforms_only()
+    {
+        return EngineOps{ENG::ELOG, ENG::LOGB, &ntt, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    }
+};
+
+}  // namespace d2

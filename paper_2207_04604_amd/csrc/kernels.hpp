@@ -1,0 +1,523 @@
+// HIP kernels of the exchange round.  One workgroup owns one polynomial (or one ciphertext
+// and walks over its RNS limbs); transforms run in registers + LDS (ntt_engine.hpp).
+#pragma once
+#include "mod64.hpp"
+#include "ntt_engine.hpp"
+#include "philox.hpp"
+
+namespace d2 {
+
+constexpr int MAX_LIMBS = 16;
+constexpr int MAX_GROUP = 64;
+
+// Per-modulus constants; entry L of the table array describes the plaintext modulus t.
+struct LimbTab {
+    uint64_t q;
+    Tw ninv;            // N^-1 mod q
+    Tw wn;              // (inverse twiddle 1) * N^-1 mod q
+    Tw lambda;          // floor(Q/t) mod q
+    Tw gamma;           // (Q/q)^-1 mod q
+    uint64_t theta_hi;  // floor(t * 2^128 / q), high and low words
+    uint64_t theta_lo;
+    const Tw *fwd;      // forward twiddles, N entries
+    const Tw *inv;      // inverse twiddles, N entries
+};
+
+struct RoundConst {
+    uint64_t t;
+    uint32_t L;
+    uint32_t eta_mask;   // low eta bits set
+    int32_t clamp;       // floor(((t-1)/2) / K_max)
+    float scale;         // 2^f
+    float inv_scale;     // 2^-f
+    PhiloxKey key;
+};
+
+struct PtrList {
+    const void *p[MAX_GROUP];
+};
+struct IdList {
+    uint32_t v[MAX_GROUP];
+};
+
+D2_DEV uint32_t bitrev(uint32_t v, int bits) { return __brev(v) >> (32 - bits); }
+
+// -------------------------------------------------------------------------------------
+// Plain batched transforms: polys [B][L][N] in place, one workgroup per (b, limb).
+// -------------------------------------------------------------------------------------
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T) k_ntt_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    const int tid = threadIdx.x;
+    const uint32_t limb = blockIdx.x % L;
+    const LimbTab &tb = tabs[limb];
+    const uint64_t q = tb.q;
+    uint64_t *p = polys + (size_t)blockIdx.x * ENG::NB;
+    uint64_t x[ENG::E];
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) x[k] = p[ENG::coef_pos(k, tid)];
+    ENG::forward(x, lds, tid, 0, tb.fwd, q);
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) p[ENG::eval_pos(k, tid)] = reduce4(x[k], q);
+}
+
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T) k_ntt_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    const int tid = threadIdx.x;
+    const uint32_t limb = blockIdx.x % L;
+    const LimbTab &tb = tabs[limb];
+    const uint64_t q = tb.q;
+    uint64_t *p = polys + (size_t)blockIdx.x * ENG::NB;
+    uint64_t x[ENG::E];
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) x[k] = p[ENG::eval_pos(k, tid)];
+    ENG::template inverse<true>(x, lds, tid, 0, tb.inv, q, tb.ninv, tb.wn);
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) p[ENG::coef_pos(k, tid)] = csub(x[k], q);
+}
+
+// -------------------------------------------------------------------------------------
+// Transforms longer than one workgroup can hold: the top LOGH = LOGN - LOGB stages couple
+// the 2^LOGH blocks of NB coefficients ("head", register-only, strided global access); the
+// remaining LOGB stages are independent per block ("tail", the engine with a block id).
+// -------------------------------------------------------------------------------------
+template <int LOGN, int LOGH>
+__global__ void __launch_bounds__(256) k_head_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L)
+{
+    constexpr int H = 1 << LOGH;
+    constexpr int STRIDE = 1 << (LOGN - LOGH);
+    const uint32_t poly = blockIdx.y;
+    const LimbTab &tb = tabs[poly % L];
+    const uint64_t q = tb.q;
+    const Tw *tw = tb.fwd;
+    uint64_t *p = polys + ((size_t)poly << LOGN) + (size_t)blockIdx.x * 256 + threadIdx.x;
+    uint64_t x[H];
+#pragma unroll
+    for (int k = 0; k < H; ++k) x[k] = p[(size_t)k * STRIDE];
+#pragma unroll
+    for (int kb = LOGH - 1; kb >= 0; --kb) {
+        const int s = LOGH - 1 - kb;
+#pragma unroll
+        for (int g = 0; g < (H >> (kb + 1)); ++g) {
+            const Tw w = tw[(1 << s) + g];
+#pragma unroll
+            for (int j = 0; j < (1 << kb); ++j) {
+                const int k0 = (g << (kb + 1)) | j;
+                ct_butterfly(x[k0], x[k0 | (1 << kb)], w.w, w.ws, q);
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < H; ++k) p[(size_t)k * STRIDE] = x[k];   // stays lazy, < 4q
+}
+
+template <int LOGN, int LOGH>
+__global__ void __launch_bounds__(256) k_head_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L)
+{
+    constexpr int H = 1 << LOGH;
+    constexpr int STRIDE = 1 << (LOGN - LOGH);
+    const uint32_t poly = blockIdx.y;
+    const LimbTab &tb = tabs[poly % L];
+    const uint64_t q = tb.q, two_q = 2 * q;
+    const Tw *tw = tb.inv;
+    uint64_t *p = polys + ((size_t)poly << LOGN) + (size_t)blockIdx.x * 256 + threadIdx.x;
+    uint64_t x[H];
+#pragma unroll
+    for (int k = 0; k < H; ++k) x[k] = p[(size_t)k * STRIDE];   // in [0, 2q)
+#pragma unroll
+    for (int kb = 0; kb < LOGH; ++kb) {
+        const int s = LOGH - 1 - kb;
+        if (kb == LOGH - 1) {                                    // last stage: fold N^-1
+#pragma unroll
+            for (int j = 0; j < (1 << kb); ++j) {
+                uint64_t a = x[j], c = x[j | (1 << kb)];
+                x[j] = mul_shoup_lazy(a + c, tb.ninv.w, tb.ninv.ws, q);
+                x[j | (1 << kb)] = mul_shoup_lazy(a - c + two_q, tb.wn.w, tb.wn.ws, q);
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < (H >> (kb + 1)); ++g) {
+                const Tw w = tw[(1 << s) + g];
+#pragma unroll
+                for (int j = 0; j < (1 << kb); ++j) {
+                    const int k0 = (g << (kb + 1)) | j;
+                    gs_butterfly(x[k0], x[k0 | (1 << kb)], w.w, w.ws, q);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < H; ++k) p[(size_t)k * STRIDE] = csub(x[k], q);
+}
+
+// tail: grid.x = blocks per polynomial, grid.y = polynomial index (b * L + limb)
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T) k_tail_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    const int tid = threadIdx.x;
+    const uint32_t poly = blockIdx.y, blk = blockIdx.x;
+    const LimbTab &tb = tabs[poly % L];
+    const uint64_t q = tb.q;
+    uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
+    uint64_t x[ENG::E];
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) x[k] = p[ENG::coef_pos(k, tid)];
+    ENG::forward(x, lds, tid, blk, tb.fwd, q);
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) p[ENG::eval_pos(k, tid)] = reduce4(x[k], q);
+}
+
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T) k_tail_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    const int tid = threadIdx.x;
+    const uint32_t poly = blockIdx.y, blk = blockIdx.x;
+    const LimbTab &tb = tabs[poly % L];
+    const uint64_t q = tb.q;
+    uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
+    uint64_t x[ENG::E];
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) x[k] = p[ENG::eval_pos(k, tid)];
+    ENG::template inverse<false>(x, lds, tid, blk, tb.inv, q, tb.ninv, tb.wn);
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) p[ENG::coef_pos(k, tid)] = x[k];   // [0, 2q), head finishes
+}
+
+// -------------------------------------------------------------------------------------
+// Sampling helpers: small polynomials are drawn block by block, staged in LDS as packed
+// words (one per coefficient, natural order) and then picked up by their pass-0 owners.
+// -------------------------------------------------------------------------------------
+// mu (ternary) in byte 0, e0 in byte 1, e1 in byte 2 (two's complement bytes)
+template <class ENG>
+D2_DEV void stage_encrypt_samples(uint32_t *lds32, int tid, uint32_t party, uint32_t group, uint32_t ct,
+                                  const RoundConst &rc)
+{
+    for (int j = tid; j < ENG::NB / 4; j += ENG::T) {
+        int32_t mu[4], e0[4], e1[4];
+        ternary4(philox4x32_10(j, ct, party, counter_tag(DOM_ENC_U, 0, group), rc.key), mu);
+        cbd2(philox4x32_10(2 * j, ct, party, counter_tag(DOM_ENC_E0, 0, group), rc.key), rc.eta_mask, e0);
+        cbd2(philox4x32_10(2 * j + 1, ct, party, counter_tag(DOM_ENC_E0, 0, group), rc.key), rc.eta_mask, e0 + 2);
+        cbd2(philox4x32_10(2 * j, ct, party, counter_tag(DOM_ENC_E1, 0, group), rc.key), rc.eta_mask, e1);
+        cbd2(philox4x32_10(2 * j + 1, ct, party, counter_tag(DOM_ENC_E1, 0, group), rc.key), rc.eta_mask, e1 + 2);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            lds32[4 * j + i] = ((uint32_t)mu[i] & 0xffu) | (((uint32_t)e0[i] & 0xffu) << 8) |
+                               (((uint32_t)e1[i] & 0xffu) << 16);
+    }
+}
+
+template <class ENG>
+D2_DEV void stage_cbd(uint32_t *lds32, int tid, uint32_t domain, uint32_t party, uint32_t group, uint32_t ct,
+                      const RoundConst &rc)
+{
+    for (int j = tid; j < ENG::NB / 2; j += ENG::T) {
+        int32_t e[2];
+        cbd2(philox4x32_10(j, ct, party, counter_tag(domain, 0, group), rc.key), rc.eta_mask, e);
+        lds32[2 * j] = (uint32_t)e[0];
+        lds32[2 * j + 1] = (uint32_t)e[1];
+    }
+}
+
+D2_DEV int32_t sbyte(uint32_t w, int i) { return (int32_t)(int8_t)(w >> (8 * i)); }
+
+// -------------------------------------------------------------------------------------
+// Fixed point + slots (encode) as a device step: leaves the plaintext polynomial of
+// ciphertext index c in registers in pass-0 (natural) ownership, values in [0, t).
+// -------------------------------------------------------------------------------------
+template <class ENG>
+D2_DEV void encode_to_regs(uint64_t (&x)[ENG::E], uint64_t *lds, int tid, const float *grad, uint64_t first,
+                           uint64_t n_values, const LimbTab &tt, const RoundConst &rc)
+{
+    const uint64_t t = tt.q;
+    __syncthreads();
+    for (int j = tid; j < ENG::NB; j += ENG::T) {
+        uint64_t gi = first + (uint64_t)j;
+        float v = gi < n_values ? grad[gi] : 0.0f;
+        float r = (v != v) ? 0.0f : __builtin_rintf(v * rc.scale);
+        float bound = (float)rc.clamp;
+        r = r > bound ? bound : r;
+        r = r < -bound ? -bound : r;
+        int32_t z = (int32_t)r;
+        lds[ENG::phys(j)] = z >= 0 ? (uint64_t)z : t - (uint64_t)(uint32_t)(-z);
+    }
+    __syncthreads();
+    // slot j is the evaluation xhat[j], which the engine keeps at block index bitrev(j)
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k)
+        x[k] = lds[ENG::phys((int)bitrev((uint32_t)(tid * ENG::E + k), ENG::LOGB))];
+    ENG::template inverse<true>(x, lds, tid, 0, tt.inv, t, tt.ninv, tt.wn);
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) x[k] = csub(x[k], t);
+}
+
+// registers hold a plaintext polynomial (natural ownership, [0,t)) -> floats
+template <class ENG>
+D2_DEV void decode_from_regs(uint64_t (&x)[ENG::E], uint64_t *lds, int tid, float *out, uint64_t first,
+                             uint64_t n_values, const LimbTab &tt, const RoundConst &rc)
+{
+    const uint64_t t = tt.q;
+    ENG::forward(x, lds, tid, 0, tt.fwd, t);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k)
+        lds[ENG::phys((int)bitrev((uint32_t)(tid * ENG::E + k), ENG::LOGB))] = reduce4(x[k], t);
+    __syncthreads();
+    for (int j = tid; j < ENG::NB; j += ENG::T) {
+        uint64_t gi = first + (uint64_t)j;
+        if (gi < n_values) {
+            uint64_t z = lds[ENG::phys(j)];
+            int32_t c = z > (t - 1) / 2 ? (int32_t)((int64_t)z - (int64_t)t) : (int32_t)z;
+            out[gi] = (float)c * rc.inv_scale;
+        }
+    }
+}
+
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T) k_encode(const float *grad, uint64_t n_values, uint64_t *pt,
+                                                   const LimbTab *tabs, RoundConst rc)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x;
+    uint64_t x[ENG::E];
+    encode_to_regs<ENG>(x, lds, tid, grad, (uint64_t)c * ENG::NB, n_values, tabs[rc.L], rc);
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) pt[(size_t)c * ENG::NB + ENG::coef_pos(k, tid)] = x[k];
+}
+
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T) k_decode(const uint64_t *pt, uint64_t n_values, float *out,
+                                                   const LimbTab *tabs, RoundConst rc)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x;
+    uint64_t x[ENG::E];
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) x[k] = pt[(size_t)c * ENG::NB + ENG::coef_pos(k, tid)];
+    decode_from_regs<ENG>(x, lds, tid, out, (uint64_t)c * ENG::NB, n_values, tabs[rc.L], rc);
+}
+
+// -------------------------------------------------------------------------------------
+// Set-up: one party's key share.  grid = L (one workgroup per limb).
+//   sk (prepared): NTT(s) and Shoup quotients;  pk0 = -(p1 s + e) in evaluation form.
+// p1 is the prepared common random polynomial.
+// -------------------------------------------------------------------------------------
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T) k_keygen(uint32_t party, uint64_t *sk, uint64_t *pk0, const uint64_t *p1,
+                                                   const LimbTab *tabs, RoundConst rc)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    uint32_t *lds32 = (uint32_t *)lds;
+    const int tid = threadIdx.x;
+    const uint32_t limb = blockIdx.x, L = rc.L;
+    const LimbTab &tb = tabs[limb];
+    const uint64_t q = tb.q;
+    const size_t LN = (size_t)L * ENG::NB, off = (size_t)limb * ENG::NB;
+    uint64_t s[ENG::E], e[ENG::E];
+    // secret share: ternary, counter (block, 0, party, SK)
+    for (int j = tid; j < ENG::NB / 4; j += ENG::T) {
+        int32_t v[4];
+        ternary4(philox4x32_10(j, 0, party, counter_tag(DOM_SK, 0, 0), rc.key), v);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lds32[4 * j + i] = (uint32_t)v[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) s[k] = lift_small((int32_t)lds32[ENG::coef_pos(k, tid)], q);
+    __syncthreads();
+    stage_cbd<ENG>(lds32, tid, DOM_PK_E, party, 0, 0, rc);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) e[k] = lift_small((int32_t)lds32[ENG::coef_pos(k, tid)], q);
+    ENG::forward(s, lds, tid, 0, tb.fwd, q);
+    ENG::forward(e, lds, tid, 0, tb.fwd, q);
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) {
+        const int pos = ENG::eval_pos(k, tid);
+        uint64_t sv = reduce4(s[k], q);
+        sk[off + pos] = sv;
+        sk[LN + off + pos] = shoup_quotient(sv, q);
+        uint64_t prod = mul_shoup(sv, p1[off + pos], p1[LN + off + pos], q);   // p1 * s
+        uint64_t sum = add_mod(prod, reduce4(e[k], q), q);
+        pk0[off + pos] = sum == 0 ? 0 : q - sum;
+    }
+}
+
+// -------------------------------------------------------------------------------------
+// BFV.Encrypt in evaluation form.  grid = (C, members); one workgroup per ciphertext.
+//   c0 = NTT(Lambda m + e0) + NTT(mu) * p0,   c1 = NTT(e1) + NTT(mu) * p1.
+// FROM_FLOAT: the plaintext is encoded on the fly from the member's gradient;
+// otherwise it is read from pt [C][N].
+// -------------------------------------------------------------------------------------
+template <class ENG, bool FROM_FLOAT>
+__global__ void __launch_bounds__(ENG::T) k_encrypt(const uint64_t *pk, PtrList src, IdList parties, uint32_t group,
+                                                    uint32_t ct_base, uint64_t n_values, uint64_t *ct, uint32_t C,
+                                                    const LimbTab *tabs, RoundConst rc)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    uint32_t *lds32 = (uint32_t *)lds;
+    constexpr int E = ENG::E;
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x, member = blockIdx.y, L = rc.L;
+    const uint32_t party = parties.v[member];
+    const size_t LN = (size_t)L * ENG::NB;
+    uint64_t *out = ct + ((size_t)member * C + c) * 2 * LN;
+
+    uint32_t m[E];
+    {
+        uint64_t x[E];
+        if (FROM_FLOAT) {
+            encode_to_regs<ENG>(x, lds, tid, (const float *)src.p[member], (uint64_t)c * ENG::NB, n_values,
+                                tabs[L], rc);
+        } else {
+            const uint64_t *pt = (const uint64_t *)src.p[member] + (size_t)c * ENG::NB;
+#pragma unroll
+            for (int k = 0; k < E; ++k) x[k] = pt[ENG::coef_pos(k, tid)];
+        }
+#pragma unroll
+        for (int k = 0; k < E; ++k) m[k] = (uint32_t)x[k];
+    }
+    uint32_t smp[E];
+    __syncthreads();
+    stage_encrypt_samples<ENG>(lds32, tid, party, group, ct_base + c, rc);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < E; ++k) smp[k] = lds32[ENG::coef_pos(k, tid)];
+
+    for (uint32_t limb = 0; limb < L; ++limb) {
+        const LimbTab &tb = tabs[limb];
+        const uint64_t q = tb.q;
+        const size_t off = (size_t)limb * ENG::NB;
+        const uint64_t *p0 = pk + off, *p0s = pk + LN + off;
+        const uint64_t *p1 = pk + 2 * LN + off, *p1s = pk + 3 * LN + off;
+        uint64_t u[E], x[E];
+#pragma unroll
+        for (int k = 0; k < E; ++k) u[k] = lift_small(sbyte(smp[k], 0), q);
+        ENG::forward(u, lds, tid, 0, tb.fwd, q);
+#pragma unroll
+        for (int k = 0; k < E; ++k)
+            x[k] = add_mod(mul_shoup((uint64_t)m[k], tb.lambda.w, tb.lambda.ws, q), lift_small(sbyte(smp[k], 1), q), q);
+        ENG::forward(x, lds, tid, 0, tb.fwd, q);
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            const int pos = ENG::eval_pos(k, tid);
+            uint64_t v = mul_shoup_lazy(u[k], p0[pos], p0s[pos], q) + x[k];   // < 6q
+            out[off + pos] = reduce4(csub(v, 4 * q), q);
+        }
+#pragma unroll
+        for (int k = 0; k < E; ++k) x[k] = lift_small(sbyte(smp[k], 2), q);
+        ENG::forward(x, lds, tid, 0, tb.fwd, q);
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            const int pos = ENG::eval_pos(k, tid);
+            uint64_t v = mul_shoup_lazy(u[k], p1[pos], p1s[pos], q) + x[k];
+            out[LN + off + pos] = reduce4(csub(v, 4 * q), q);
+        }
+    }
+}
+
+// -------------------------------------------------------------------------------------
+// Decryption share h = s c1 + e in evaluation form.  grid = (C, members).
+// ct: [C][2][L][N] (the aggregate); share buffer of member m: shares + m * share_stride.
+// -------------------------------------------------------------------------------------
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T) k_share(PtrList sks, IdList parties, uint32_t group, uint32_t ct_base,
+                                                  const uint64_t *ct, uint64_t *shares, size_t share_stride,
+                                                  const LimbTab *tabs, RoundConst rc)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    uint32_t *lds32 = (uint32_t *)lds;
+    constexpr int E = ENG::E;
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x, member = blockIdx.y, L = rc.L;
+    const size_t LN = (size_t)L * ENG::NB;
+    const uint64_t *sk = (const uint64_t *)sks.p[member];
+    const uint64_t *c1 = ct + ((size_t)c * 2 + 1) * LN;
+    uint64_t *out = shares + (size_t)member * share_stride + (size_t)c * LN;
+    int32_t e[E];
+    stage_cbd<ENG>(lds32, tid, DOM_DEC_E, parties.v[member], group, ct_base + c, rc);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < E; ++k) e[k] = (int32_t)lds32[ENG::coef_pos(k, tid)];
+    for (uint32_t limb = 0; limb < L; ++limb) {
+        const LimbTab &tb = tabs[limb];
+        const uint64_t q = tb.q;
+        const size_t off = (size_t)limb * ENG::NB;
+        uint64_t x[E];
+#pragma unroll
+        for (int k = 0; k < E; ++k) x[k] = lift_small(e[k], q);
+        ENG::forward(x, lds, tid, 0, tb.fwd, q);
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            const int pos = ENG::eval_pos(k, tid);
+            uint64_t v = mul_shoup_lazy(c1[off + pos], sk[off + pos], sk[LN + off + pos], q) + x[k];
+            out[off + pos] = reduce4(csub(v, 4 * q), q);
+        }
+    }
+}
+
+// -------------------------------------------------------------------------------------
+// Combine: y = c0 + sum_k h_k, back to coefficient form, then pt = round(t y / Q) mod t
+// by summing t * y_i' / q_i over the limbs with y_i' = y_i (Q/q_i)^-1 mod q_i: integer
+// parts exactly, fractional parts in 64-bit fixed point (each term is truncated by less
+// than 2^-63, so the rounding is exact unless t y / Q lies within L * 2^-63 of a half-integer).
+// grid = C.  DECODE: continue to floats instead of storing the plaintext polynomial.
+// -------------------------------------------------------------------------------------
+template <class ENG, bool DECODE>
+__global__ void __launch_bounds__(ENG::T) k_combine(const uint64_t *ct, PtrList shares, uint32_t K, uint64_t *pt,
+                                                    float *out, uint64_t n_values, const LimbTab *tabs, RoundConst rc)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    constexpr int E = ENG::E;
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x, L = rc.L;
+    const size_t LN = (size_t)L * ENG::NB;
+    const uint64_t *c0 = ct + (size_t)c * 2 * LN;
+    uint64_t acc_int[E], acc_frac[E];
+#pragma unroll
+    for (int k = 0; k < E; ++k) { acc_int[k] = 0; acc_frac[k] = 0; }
+    for (uint32_t limb = 0; limb < L; ++limb) {
+        const LimbTab &tb = tabs[limb];
+        const uint64_t q = tb.q;
+        const size_t off = (size_t)limb * ENG::NB;
+        uint64_t x[E];
+#pragma unroll
+        for (int k = 0; k < E; ++k) x[k] = c0[off + ENG::eval_pos(k, tid)];
+        for (uint32_t j = 0; j < K; ++j) {
+            const uint64_t *h = (const uint64_t *)shares.p[j] + (size_t)c * LN + off;
+#pragma unroll
+            for (int k = 0; k < E; ++k) x[k] = add_mod(x[k], h[ENG::eval_pos(k, tid)], q);
+        }
+        ENG::template inverse<true>(x, lds, tid, 0, tb.inv, q, tb.ninv, tb.wn);
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            uint64_t y = mul_shoup(csub(x[k], q), tb.gamma.w, tb.gamma.ws, q);   // y_i'
+            // y * theta / 2^128 = integer part, next 64 bits = fraction (theta = floor(t 2^128 / q))
+            uint64_t hi_lo = y * tb.theta_hi, hi_hi = __umul64hi(y, tb.theta_hi);
+            uint64_t lo_hi = __umul64hi(y, tb.theta_lo);
+            uint64_t frac = hi_lo + lo_hi;
+            uint64_t ip = hi_hi + (frac < hi_lo ? 1 : 0);
+            uint64_t nf = acc_frac[k] + frac;
+            acc_int[k] += ip + (nf < frac ? 1 : 0);
+            acc_frac[k] = nf;
+        }
+    }
+    const uint64_t t = rc.t;
+    uint64_t m[E];
+#pragma unroll
+    for (int k = 0; k < E; ++k) m[k] = (acc_int[k] + (acc_frac[k] >> 63)) % t;   // + 1/2, floor
+    if (DECODE) {
+        decode_from_regs<ENG>(m, lds, tid, out, (uint64_t)c * ENG::NB, n_values, tabs[L], rc);
+    } else {
+#pragma unroll
+        for (int k = 0; k < E; ++k) pt[(size_t)c * ENG::NB + ENG::coef_pos(k, tid)] = m[k];
+    }
+}
+
+}  // namespace d2

@@ -1,0 +1,169 @@
+// Workgroup-level negacyclic NTT for gfx950: register windows + LDS exchanges.
+//
+// A workgroup of T = NB / E threads transforms a block of NB = 2^LOGB coefficients that
+// is part of a length-2^LOGN transform (LOGB == LOGN: the whole polynomial).  Every thread
+// keeps E = 2^ELOG coefficients in registers.  The LOGB butterfly stages are grouped into
+// passes of (up to) ELOG stages; during a pass a thread owns the E coefficients whose
+// index differs only in the ELOG-bit "window" of that pass, so all butterflies of the
+// pass are register-to-register.  Between passes the coefficients change owner through
+// LDS (write at the old owner, barrier, read at the new owner).
+//
+// Forward transform: merged Cooley-Tukey stages (the psi twist is folded into the
+// twiddles), natural-order input, stage s pairs indices that differ in bit LOGN-1-s and
+// uses twiddle table entry 2^s + (index >> (LOGN-s)); entry k of the forward table holds
+// psi^bitrev(k).  The inverse transform runs Gentleman-Sande stages in the opposite
+// order with the inverse table (entry k holds psi^-bitrev(k)) and folds N^-1 into its
+// last stage.
+//
+// Index of a coefficient inside the block during pass p with window base wb:
+//     idx = (tid >> wb) << (wb + ELOG) | k << wb | (tid & (2^wb - 1)),   k = register slot.
+// Pass 0 has wb = LOGB - ELOG (idx = k * T + tid: coalesced natural order); the last pass
+// has wb = 0 (idx = tid * E + k), and evaluation-form data is stored at position
+// k * T + tid, so global accesses are coalesced on both sides.
+#pragma once
+#include "mod64.hpp"
+
+namespace d2 {
+
+template <int LOGN_, int ELOG_, int LOGB_ = LOGN_>
+struct Engine {
+    static constexpr int LOGN = LOGN_, ELOG = ELOG_, LOGB = LOGB_;
+    static constexpr int NB = 1 << LOGB;
+    static constexpr int E = 1 << ELOG;
+    static constexpr int T = NB / E;
+    static constexpr int NPASS = (LOGB + ELOG - 1) / ELOG;
+    static constexpr int LDS_WORDS = NB + (NB >> ELOG);   // one pad word per E coefficients
+
+    static_assert(LOGB >= ELOG && LOGB <= LOGN, "bad engine shape");
+
+    // number of stages of pass p and the window base
+    static constexpr int stages(int p) { return p < NPASS - 1 ? ELOG : LOGB - ELOG * (NPASS - 1); }
+    static constexpr int wbase(int p) { return p < NPASS - 1 ? LOGB - ELOG * (p + 1) : 0; }
+    // lowest stage bit (position inside the block index) handled by pass p
+    static constexpr int sbit(int p) { return p < NPASS - 1 ? wbase(p) : 0; }
+
+    template <int P>
+    D2_DEV static int index_of(int k, int tid)
+    {
+        constexpr int wb = wbase(P);
+        return ((tid >> wb) << (wb + ELOG)) | (k << wb) | (tid & ((1 << wb) - 1));
+    }
+
+    D2_DEV static int phys(int idx) { return idx + (idx >> ELOG); }
+
+    // position of register slot k of thread tid in evaluation-form storage of the block
+    D2_DEV static int eval_pos(int k, int tid) { return k * T + tid; }
+    // position in natural (coefficient) order during pass 0
+    D2_DEV static int coef_pos(int k, int tid) { return k * T + tid; }
+
+    template <int P>
+    D2_DEV static void fwd_pass(uint64_t (&x)[E], int tid, uint32_t blk, const Tw *__restrict__ tw,
+                                uint64_t q)
+    {
+        constexpr int wb = wbase(P), lo = sbit(P), r = stages(P);
+        const uint32_t hi = (uint32_t)(tid >> wb);
+#pragma unroll
+        for (int b = lo + r - 1; b >= lo; --b) {           // stage bit inside the block index
+            const int kb = b - wb;                         // bit inside the register slot
+            const int s = LOGN - 1 - b;                    // stage number of the transform
+            // twiddle index = 2^s + (global index >> (b + 1))
+            const uint32_t base = (1u << s) + (blk << (LOGB - b - 1)) + (hi << (ELOG - kb - 1));
+#pragma unroll
+            for (int g = 0; g < (E >> (kb + 1)); ++g) {    // distinct twiddles of this stage
+                const Tw w = tw[base + g];
+#pragma unroll
+                for (int j = 0; j < (1 << kb); ++j) {
+                    const int k0 = (g << (kb + 1)) | j;
+                    ct_butterfly(x[k0], x[k0 | (1 << kb)], w.w, w.ws, q);
+                }
+            }
+        }
+    }
+
+    // FOLD: this pass contains the last stage of the whole inverse transform (bit LOGN-1)
+    // and multiplies by N^-1 there: ninv = N^-1, wn = (inverse twiddle 1) * N^-1.
+    template <int P, bool FOLD>
+    D2_DEV static void inv_pass(uint64_t (&x)[E], int tid, uint32_t blk, const Tw *__restrict__ tw,
+                                uint64_t q, Tw ninv, Tw wn)
+    {
+        constexpr int wb = wbase(P), lo = sbit(P), r = stages(P);
+        const uint32_t hi = (uint32_t)(tid >> wb);
+#pragma unroll
+        for (int b = lo; b < lo + r; ++b) {
+            const int kb = b - wb;
+            const int s = LOGN - 1 - b;
+            const uint32_t base = (1u << s) + (blk << (LOGB - b - 1)) + (hi << (ELOG - kb - 1));
+            if (FOLD && b == LOGN - 1) {
+                const uint64_t two_q = 2 * q;
+#pragma unroll
+                for (int j = 0; j < (1 << kb); ++j) {
+                    uint64_t a = x[j], c = x[j | (1 << kb)];
+                    x[j] = mul_shoup_lazy(a + c, ninv.w, ninv.ws, q);
+                    x[j | (1 << kb)] = mul_shoup_lazy(a - c + two_q, wn.w, wn.ws, q);
+                }
+            } else {
+#pragma unroll
+                for (int g = 0; g < (E >> (kb + 1)); ++g) {
+                    const Tw w = tw[base + g];
+#pragma unroll
+                    for (int j = 0; j < (1 << kb); ++j) {
+                        const int k0 = (g << (kb + 1)) | j;
+                        gs_butterfly(x[k0], x[k0 | (1 << kb)], w.w, w.ws, q);
+                    }
+                }
+            }
+        }
+    }
+
+    // Hand the coefficients from the owners of pass PF to the owners of pass PT.
+    template <int PF, int PT>
+    D2_DEV static void exchange(uint64_t (&x)[E], uint64_t *lds, int tid)
+    {
+        __syncthreads();                       // earlier readers of lds are done
+#pragma unroll
+        for (int k = 0; k < E; ++k) lds[phys(index_of<PF>(k, tid))] = x[k];
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < E; ++k) x[k] = lds[phys(index_of<PT>(k, tid))];
+    }
+
+    template <int P>
+    D2_DEV static void fwd_from(uint64_t (&x)[E], uint64_t *lds, int tid, uint32_t blk,
+                                const Tw *__restrict__ tw, uint64_t q)
+    {
+        fwd_pass<P>(x, tid, blk, tw, q);
+        if constexpr (P + 1 < NPASS) {
+            exchange<P, P + 1>(x, lds, tid);
+            fwd_from<P + 1>(x, lds, tid, blk, tw, q);
+        }
+    }
+
+    template <int P, bool FOLD>
+    D2_DEV static void inv_from(uint64_t (&x)[E], uint64_t *lds, int tid, uint32_t blk,
+                                const Tw *__restrict__ tw, uint64_t q, Tw ninv, Tw wn)
+    {
+        inv_pass<P, FOLD>(x, tid, blk, tw, q, ninv, wn);
+        if constexpr (P > 0) {
+            exchange<P, P - 1>(x, lds, tid);
+            inv_from<P - 1, FOLD>(x, lds, tid, blk, tw, q, ninv, wn);
+        }
+    }
+
+    // x: pass-0 ownership, values in [0, 4q)  ->  last-pass ownership, values in [0, 4q).
+    D2_DEV static void forward(uint64_t (&x)[E], uint64_t *lds, int tid, uint32_t blk,
+                               const Tw *__restrict__ tw, uint64_t q)
+    {
+        fwd_from<0>(x, lds, tid, blk, tw, q);
+    }
+
+    // x: last-pass ownership, values in [0, 2q)  ->  pass-0 ownership, values in [0, 2q),
+    // scaled by N^-1 when FOLD.
+    template <bool FOLD>
+    D2_DEV static void inverse(uint64_t (&x)[E], uint64_t *lds, int tid, uint32_t blk,
+                               const Tw *__restrict__ tw, uint64_t q, Tw ninv, Tw wn)
+    {
+        inv_from<NPASS - 1, FOLD>(x, lds, tid, blk, tw, q, ninv, wn);
+    }
+};
+
+}  // namespace d2

@@ -1,0 +1,88 @@
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as 1, 2, 3",
+// SC'11) and the three coefficient samplers, evaluated per lane in registers.
+//
+// Counter = (block, ciphertext index, party, domain | limb << 8 | group << 16);
+// key = (seed low word, seed high word).  The key schedule is added after every round.
+#pragma once
+#include <stdint.h>
+
+#ifndef D2_DEV
+#define D2_DEV __device__ __forceinline__
+#endif
+
+namespace d2 {
+
+enum : uint32_t {
+    DOM_SK = 1, DOM_PK_E = 2, DOM_CRS = 3, DOM_ENC_U = 4, DOM_ENC_E0 = 5, DOM_ENC_E1 = 6,
+    DOM_DEC_E = 7, DOM_BENCH = 8
+};
+
+struct PhiloxKey { uint32_t k0, k1; };
+
+struct Block4 { uint32_t w[4]; };
+
+D2_DEV Block4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, PhiloxKey key)
+{
+    uint32_t k0 = key.k0, k1 = key.k1;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        uint32_t lo0 = 0xD2511F53u * c0, hi0 = __umulhi(0xD2511F53u, c0);
+        uint32_t lo1 = 0xCD9E8D57u * c2, hi1 = __umulhi(0xCD9E8D57u, c2);
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    Block4 b;
+    b.w[0] = c0; b.w[1] = c1; b.w[2] = c2; b.w[3] = c3;
+    return b;
+}
+
+D2_DEV uint32_t counter_tag(uint32_t domain, uint32_t limb, uint32_t group)
+{
+    return domain | (limb << 8) | (group << 16);
+}
+
+// Ternary values of coefficients 4b..4b+3 from block b: floor(3w / 2^32) - 1.
+D2_DEV void ternary4(const Block4 &b, int32_t out[4])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out[i] = (int32_t)__umulhi(b.w[i], 3u) - 1;
+}
+
+// Centred-binomial values of coefficients 2b, 2b+1 from block b.
+D2_DEV void cbd2(const Block4 &b, uint32_t mask, int32_t out[2])
+{
+    out[0] = __popc(b.w[0] & mask) - __popc(b.w[1] & mask);
+    out[1] = __popc(b.w[2] & mask) - __popc(b.w[3] & mask);
+}
+
+// The 128-bit little-endian value of a block reduced mod q (q < 2^61): Horner over the
+// four words with 64-bit remainders.
+D2_DEV uint64_t uniform_mod(const Block4 &b, uint64_t q)
+{
+    // r = ((w3 * 2^32 + w2) * 2^32 + w1) * 2^32 + w0 mod q, keeping r < q < 2^61
+    uint64_t r = 0;
+#pragma unroll
+    for (int i = 3; i >= 0; --i) {
+        // r * 2^32 + w mod q without overflow: shift in four 8-bit steps (r < 2^61 -> r<<3 fits... )
+        // do it as 32 single-bit doublings is wasteful; use two 16-bit steps with 128-bit-free reduction:
+        uint64_t hi = r;
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {           // 16 x (2 bits): hi*4 < 2^63
+            hi <<= 2;
+            // hi < 4q: bring back under q
+            if (hi >= 2 * q) hi -= 2 * q;
+            if (hi >= q) hi -= q;
+        }
+        uint64_t w = b.w[i];
+        w %= q;                                  // no-op unless q < 2^32
+        r = hi + w;
+        if (r >= q) r -= q;
+    }
+    return r;
+}
+
+}  // namespace d2

@@ -1,0 +1,56 @@
+// Element-wise kernels that do not depend on the engine shape (included by one translation unit).
+#pragma once
+#include "kernels.hpp"
+
+namespace d2 {
+
+// -------------------------------------------------------------------------------------
+// Uniform polynomials in coefficient form: out [B][L][N]; Philox counter
+// (n, ct = b, party = 0, domain | limb << 8).
+// -------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_uniform(uint64_t *out, const LimbTab *tabs, uint32_t L, uint32_t log2n,
+                                                 uint32_t domain, PhiloxKey key, size_t total)
+{
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    uint32_t n = (uint32_t)(i & ((1u << log2n) - 1));
+    size_t poly = i >> log2n;
+    uint32_t limb = (uint32_t)(poly % L), b = (uint32_t)(poly / L);
+    Block4 blk = philox4x32_10(n, b, 0, counter_tag(domain, limb, 0), key);
+    out[i] = uniform_mod(blk, tabs[limb].q);
+}
+
+// values [L][N] (canonical) -> prepared polynomial: copy + Shoup quotients.
+// K > 0: the values are the sum of K inputs.
+__global__ void __launch_bounds__(256) k_prepare(uint64_t *dst, PtrList src, uint32_t K, const LimbTab *tabs,
+                                                 uint32_t log2n, size_t total)
+{
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    uint64_t q = tabs[i >> log2n].q;
+    uint64_t v = 0;
+    for (uint32_t k = 0; k < K; ++k) v = add_mod(v, ((const uint64_t *)src.p[k])[i], q);
+    dst[i] = v;
+    dst[total + i] = shoup_quotient(v, q);
+}
+
+// -------------------------------------------------------------------------------------
+// dst = sum of K ciphertext buffers (BFV.Add), elementwise over `total` words laid out
+// [..][L][N]; K inputs by pointer; ACC: dst is also an input.
+// -------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_sum(uint64_t *dst, PtrList src, uint32_t K, const LimbTab *tabs, uint32_t L,
+                                             uint32_t log2n, size_t total)
+{
+    size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 2;
+    if (i >= total) return;
+    uint64_t q = tabs[(i >> log2n) % L].q;
+    ulonglong2 acc = *(const ulonglong2 *)((const uint64_t *)src.p[0] + i);
+    for (uint32_t k = 1; k < K; ++k) {
+        ulonglong2 v = *(const ulonglong2 *)((const uint64_t *)src.p[k] + i);
+        acc.x = add_mod(acc.x, v.x, q);
+        acc.y = add_mod(acc.y, v.y, q);
+    }
+    *(ulonglong2 *)(dst + i) = acc;
+}
+
+}  // namespace d2

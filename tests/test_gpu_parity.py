@@ -1,0 +1,261 @@
+"""Parity of the HIP library with the CPU oracle, through the C ABI, on a real MI355X.
+
+Bar: bit-exact on every coefficient of every key, ciphertext, share and plaintext, and
+0 ulp on the decoded floats (the arithmetic is integer; the float steps are exact)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from oracle import oracle as O
+from paper_2207_04604_amd import binding as B
+from paper_2207_04604_amd.synth import CONFIGS, toy_config
+
+from gpu_util import DEV, Keys, dzeros, make_ctx, make_pair, to_dev, to_eval, to_host
+
+
+def fixed_point_sum(grads, f, clamp):
+    """sum_k clamp(rint(v_k 2^f)) 2^-f, in numpy: what every round must decode to."""
+    acc = np.zeros(grads[0].shape, dtype=np.int64)
+    for g in grads:
+        r = np.rint(g.astype(np.float32) * np.float32(2.0 ** f))
+        r = np.where(np.isnan(r), 0, r)
+        acc += np.clip(r, -clamp, clamp).astype(np.int64)
+    return (acc.astype(np.float32) * np.float32(2.0 ** -f)).astype(np.float32)
+
+
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,batch", [("C1", 3), ("C2", 3), ("C3", 2), ("C4", 2), ("C5", 2)])
+def test_transforms_on_every_prime_set(name, batch):
+    cfg = CONFIGS[name]
+    o = O.Oracle(cfg.log2_n, cfg.q, 0, 21, 0, 1, cfg.seed)
+    ctx = make_ctx(cfg.log2_n, cfg.q, 0, seed=cfg.seed)
+    perm = ctx.index_map()
+    assert sorted(perm.tolist()) == list(range(cfg.N))
+    for i in range(cfg.L):
+        assert ctx.root(i) == o.psi[i]
+    polys = o.bench_polys(batch)
+    d = dzeros(batch * cfg.L * cfg.N)
+    ctx.bench_polys(d, batch)
+    assert np.array_equal(to_host(d, polys.shape), polys), "uniform sampling"
+    ctx.ntt_forward(d, batch)
+    assert np.array_equal(to_host(d, polys.shape), to_eval(o, perm, polys)), "forward transform"
+    ctx.ntt_inverse(d, batch)
+    assert np.array_equal(to_host(d, polys.shape), polys), "inverse transform"
+    # inverse alone, from oracle-made evaluation data with extreme values
+    edge = polys.copy()
+    for i in range(cfg.L):
+        edge[0, i, :4] = [0, 1, cfg.q[i] - 1, cfg.q[i] - 2]
+    d = to_dev(to_eval(o, perm, edge).reshape(-1))
+    ctx.ntt_inverse(d, batch)
+    assert np.array_equal(to_host(d, polys.shape), edge), "inverse of oracle data"
+    ctx.close()
+
+
+def test_transform_full_batch_C5_roundtrip_and_samples():
+    """The micro-benchmark configuration at full size (64 x 16 polynomials of 65536): the
+    round trip returns the input, and sampled polynomials match the oracle's transform."""
+    cfg = CONFIGS["C5"]
+    o = O.Oracle(cfg.log2_n, cfg.q, 0, 21, 0, 1, cfg.seed)
+    ctx = make_ctx(cfg.log2_n, cfg.q, 0, seed=cfg.seed)
+    perm = ctx.index_map()
+    Bn = cfg.batch
+    d = dzeros(Bn * cfg.L * cfg.N)
+    ctx.bench_polys(d, Bn)
+    ref = d.clone()
+    ctx.ntt_forward(d, Bn)
+    fwd = to_host(d, (Bn, cfg.L, cfg.N))
+    for (b, i) in [(0, 0), (17, 5), (63, 15)]:
+        x = O.sample_uniform(cfg.seed, O.DOM_BENCH, i, 0, 0, b, cfg.q[i], cfg.N)
+        assert np.array_equal(to_host(ref, (Bn, cfg.L, cfg.N))[b, i], x)
+        assert np.array_equal(fwd[b, i], O.ntt_forward(x, cfg.q[i], o.psi[i])[perm]), (b, i)
+    assert not torch.equal(d, ref)
+    ctx.ntt_inverse(d, Bn)
+    assert torch.equal(d, ref), "round trip"
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------------------
+def run_calls_and_compare(cfg, o, ctx, perm, keys, members, group, grads, ct_base=0, check_cts=True):
+    """The per-call path for one group; every intermediate object is compared."""
+    L, N = o.L, o.N
+    n_values = grads[members[0]].size
+    C_ = (n_values + N - 1) // N
+    opk, dpk = keys.group_pk(members, perm)
+    dagg, oagg = None, None
+    for k in members:
+        dgrad = to_dev(grads[k])
+        dpt = dzeros(C_ * N)
+        ctx.encode(dgrad, n_values, dpt, C_)
+        opt = o.encode(grads[k])
+        assert np.array_equal(to_host(dpt, (C_, N)), opt), f"plaintext of party {k}"
+        dct = dzeros(C_ * 2 * L * N)
+        ctx.encrypt(dpk, dpt, C_, k, group, ct_base, dct)
+        oct_ = o.encrypt(opk, opt, k, group, ct_base)
+        if check_cts:
+            assert np.array_equal(to_host(dct, oct_.shape), to_eval(o, perm, oct_)), f"ciphertexts of party {k}"
+        if dagg is None:
+            dagg, oagg = dct, oct_
+        else:
+            ctx.add(dagg, dct, C_)
+            oagg = o.add(oagg, oct_)
+    assert np.array_equal(to_host(dagg, oagg.shape), to_eval(o, perm, oagg)), "aggregate"
+    dshares, oshares = [], []
+    for k in members:
+        dsh = dzeros(C_ * L * N)
+        ctx.partial_decrypt(keys.sk[k], dagg, C_, k, group, ct_base, dsh)
+        osh = o.partial_decrypt(keys.osk[k], oagg, k, group, ct_base)
+        assert np.array_equal(to_host(dsh, osh.shape), to_eval(o, perm, osh)), f"share of party {k}"
+        dshares.append(dsh)
+        oshares.append(osh)
+    dout = dzeros(C_ * N)
+    ctx.combine(dagg, dshares, C_, dout)
+    oout = o.combine(oagg, oshares)
+    assert np.array_equal(to_host(dout, (C_, N)), oout), "combined plaintext"
+    dres = torch.zeros(n_values, dtype=torch.float32, device=DEV)
+    ctx.decode(dout, C_, n_values, dres)
+    ores = o.decode(oout, n_values)
+    assert np.array_equal(dres.cpu().numpy(), ores), "decoded sum"
+    expect = fixed_point_sum([grads[k] for k in members], cfg.frac_bits, o.encode_clamp())
+    assert np.array_equal(ores, expect), "oracle decodes to the fixed-point sum"
+    return dpk, opk, to_host(dagg, oagg.shape)
+
+
+def run_fused(ctx, o, dpk, keys, members, group, grads, n_values):
+    K = len(members)
+    nbytes = ctx.round_scratch_bytes(K, n_values)
+    scratch = dzeros(nbytes // 8)
+    out = torch.zeros(n_values, dtype=torch.float32, device=DEV)
+    dgr = [to_dev(grads[k]) for k in members]
+    ctx.round_group(dpk, [keys.sk[k] for k in members], dgr, members, group, n_values, out, scratch, nbytes)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), scratch
+
+
+def test_round_C1_every_coefficient():
+    cfg = CONFIGS["C1"]
+    o, ctx, perm = make_pair(cfg)
+    grads = cfg.gradients()
+    keys = Keys(o, ctx, perm, range(cfg.parties))
+    members = cfg.groups()[0]
+    assert members == [0, 1, 2, 3]
+    dpk, opk, agg = run_calls_and_compare(cfg, o, ctx, perm, keys, members, 0, grads)
+    res, scratch = run_fused(ctx, o, dpk, keys, members, 0, grads, cfg.n_values)
+    assert np.array_equal(res, fixed_point_sum(grads, cfg.frac_bits, o.encode_clamp()))
+    # the fused path leaves the same aggregate in its scratch as the per-call path built
+    K, C_, L, N = 4, cfg.C, cfg.L, cfg.N
+    s = to_host(scratch)
+    assert np.array_equal(s[K * C_ * 2 * L * N:(K + 1) * C_ * 2 * L * N].reshape(agg.shape), agg)
+    ctx.close()
+
+
+def test_round_C2_two_groups_every_coefficient_and_all_groups_fused():
+    cfg = CONFIGS["C2"]
+    o, ctx, perm = make_pair(cfg)
+    grads = cfg.gradients()
+    keys = Keys(o, ctx, perm, range(cfg.parties))
+    groups = cfg.groups()
+    assert len(groups) == 16 and all(len(g) == 5 for g in groups)
+    for g in (0, 9):
+        run_calls_and_compare(cfg, o, ctx, perm, keys, groups[g], g, grads)
+    for g, members in enumerate(groups):
+        opk, dpk = keys.group_pk(members, perm, check=(g % 5 == 0))
+        res, _ = run_fused(ctx, o, dpk, keys, members, g, grads, cfg.n_values)
+        expect = fixed_point_sum([grads[k] for k in members], cfg.frac_bits, o.encode_clamp())
+        assert np.array_equal(res, expect), f"group {g}"
+        if g in (3, 15):      # the oracle's whole round for these groups
+            ores, _ = o.round_group(opk, [keys.osk[k] for k in members], [grads[k] for k in members], members, g)
+            assert np.array_equal(res, ores)
+    ctx.close()
+
+
+@pytest.mark.parametrize("name,group_index,sample", [("C3", 11, (0, 76, 152)), ("C4", 0, (0, 341, 683))])
+def test_round_full_size_sampled_against_oracle(name, group_index, sample):
+    """One whole group at the configuration's full size in the launch shape the benchmark
+    times; the oracle recomputes the sampled ciphertext indices one by one, and the decoded
+    result is checked everywhere against the fixed-point sum (holds at any size)."""
+    cfg = CONFIGS[name]
+    o, ctx, perm = make_pair(cfg)
+    groups = cfg.groups()
+    members = groups[group_index]
+    K, L, N, C_ = len(members), cfg.L, cfg.N, cfg.C
+    all_grads = cfg.gradients()
+    grads = {k: all_grads[k] for k in members}
+    del all_grads
+    keys = Keys(o, ctx, perm, members)
+    opk, dpk = keys.group_pk(members, perm)
+    res, scratch = run_fused(ctx, o, dpk, keys, members, group_index, grads, cfg.n_values)
+    expect = fixed_point_sum([grads[k] for k in members], cfg.frac_bits, o.encode_clamp())
+    assert np.array_equal(res, expect)
+    LN = L * N
+    cts = scratch[:K * C_ * 2 * LN].view(K, C_, 2 * LN)
+    agg = scratch[K * C_ * 2 * LN:(K + 1) * C_ * 2 * LN].view(C_, 2 * LN)
+    shares = scratch[(K + 1) * C_ * 2 * LN:(K + 1) * C_ * 2 * LN + K * C_ * LN].view(K, C_, LN)
+    for c in sample:
+        lo, hi = c * N, min((c + 1) * N, cfg.n_values)
+        oagg = None
+        for m, k in enumerate(members):
+            oct_ = o.encrypt(opk, o.encode(grads[k][lo:hi]), k, group_index, c)
+            assert np.array_equal(to_host(cts[m, c], (1, 2, L, N)), to_eval(o, perm, oct_)), (c, k)
+            oagg = oct_ if oagg is None else o.add(oagg, oct_)
+        assert np.array_equal(to_host(agg[c], (1, 2, L, N)), to_eval(o, perm, oagg)), c
+        oshares = []
+        for m, k in enumerate(members):
+            osh = o.partial_decrypt(keys.osk[k], oagg, k, group_index, c)
+            assert np.array_equal(to_host(shares[m, c], (1, L, N)), to_eval(o, perm, osh)), (c, k)
+            oshares.append(osh)
+        odec = o.decode(o.combine(oagg, oshares), hi - lo)
+        assert np.array_equal(res[lo:hi], odec), c
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------------------
+def test_edge_cases_ragged_tail_clamp_and_extreme_ids():
+    q = O.find_primes(54, 11, 2)
+    cfg = toy_config(11, q, 12289, parties=3, n_values=2 * 2048 + 5, frac_bits=6)
+    o, ctx, perm = make_pair(cfg, max_group=3)
+    rng = np.random.default_rng(11)
+    grads = {k: rng.normal(0, 8.0, cfg.n_values).astype(np.float32) for k in (0, 40000, 65535)}
+    grads[0][:10] = [np.nan, np.inf, -np.inf, 1e30, -1e30, 0.5 / 64, 1.5 / 64, -2.5 / 64, 31.99, -0.0]
+    members = [0, 40000, 65535]
+    keys = Keys(o, ctx, perm, members)
+    dpk, opk, _ = run_calls_and_compare(cfg, o, ctx, perm, keys, members, 65535, grads, ct_base=2 ** 32 - 4)
+    res, _ = run_fused(ctx, o, dpk, keys, members, 65535, grads, cfg.n_values)
+    assert np.array_equal(res, fixed_point_sum([grads[k] for k in members], 6, o.encode_clamp()))
+    # a single value, a single party
+    one = {0: np.array([0.734], dtype=np.float32)}
+    cfg1 = toy_config(11, q, 12289, parties=1, n_values=1, frac_bits=6)
+    run_calls_and_compare(cfg1, o, ctx, perm, keys, [0], 0, one)
+    # empty requests are accepted and touch nothing
+    guard = dzeros(16)
+    ctx.encode(None, 0, guard, 0)
+    ctx.encrypt(dpk, guard, 0, 0, 0, 0, guard)
+    ctx.add(guard, guard, 0)
+    ctx.partial_decrypt(keys.sk[0], guard, 0, 0, 0, 0, guard)
+    ctx.ntt_forward(guard, 0)
+    torch.cuda.synchronize()
+    assert int(guard.abs().sum()) == 0
+    # requests outside the documented ranges are refused on the host
+    for bad in (lambda: ctx.encrypt(dpk, guard, 1, 70000, 0, 0, guard),
+                lambda: ctx.encrypt(dpk, guard, 2, 0, 0, 2 ** 32 - 1, guard),
+                lambda: ctx.combine(guard, [guard] * 4, 1, guard),
+                lambda: ctx.encode(guard, 4097, guard, 2)):
+        with pytest.raises(B.D2mheError) as ei:
+            bad()
+        assert ei.value.status == B.ERR_RANGE
+    ctx.close()
+
+
+def test_eta_and_small_prime_variants():
+    """eta = 1 and eta = 32 (full words), a 30-bit prime next to 61-bit-class primes."""
+    for (eta, bits, L, log2n) in [(1, 30, 1, 10), (32, 60, 2, 10), (7, 36, 4, 12)]:
+        q = O.find_primes(bits, log2n, L)
+        cfg = toy_config(log2n, q, 12289 if log2n == 10 else 65537, parties=2, n_values=(1 << log2n) + 3, frac_bits=3)
+        cfg.eta = eta
+        o, ctx, perm = make_pair(cfg, max_group=2)
+        rng = np.random.default_rng(eta)
+        grads = {k: rng.normal(0, 1.0, cfg.n_values).astype(np.float32) for k in (0, 1)}
+        keys = Keys(o, ctx, perm, [0, 1])
+        run_calls_and_compare(cfg, o, ctx, perm, keys, [0, 1], 2, grads)
+        ctx.close()
