@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the exchange round on one MI355X.
+
+A step is one whole round of the hot path (encode + encrypt, homomorphic sum, decryption
+shares, combine + decode) for every group of the workload, with the float32 gradients and
+all keys already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu] [--no-ntt]
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0                      # MI355X HBM3E
+VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T lane-ops/s
+MULS_PER_BUTTERFLY = 10                    # 32-bit multiplies of one 64-bit Shoup butterfly
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-ntt", action="store_true", help="skip the transform micro-benchmark")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (all parties are simulated on one device); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2207_04604_amd import binding
+    from paper_2207_04604_amd.synth import CONFIGS
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream()
+    sptr = stream.cuda_stream
+
+    def dz(n, dtype=torch.int64):
+        return torch.zeros(n, dtype=dtype, device=dev)
+
+    cfg = CONFIGS[args.workload]
+    N, L, C_, P = cfg.N, cfg.L, cfg.C, cfg.parties
+    groups = cfg.groups()
+    G, J = len(groups), sum(len(g) for g in groups)
+    ctx = binding.Context(cfg.log2_n, cfg.q, cfg.t, cfg.eta, cfg.frac_bits, cfg.max_group, cfg.seed,
+                          alloc=lambda n: dz(n // 8 + 2))
+    # ---- set-up (untimed: executed once per training run) ---------------------------------
+    grads_host = cfg.gradients()
+    grads = [torch.from_numpy(g).to(dev) for g in grads_host]
+    sks = [dz(2 * L * N) for _ in range(P)]
+    pk0 = [dz(L * N) for _ in range(P)]
+    for k in range(P):
+        ctx.keygen_share(k, sks[k], pk0[k], sptr)
+    pks = []
+    for g in groups:
+        pk = dz(4 * L * N)
+        ctx.aggregate_pk([pk0[k] for k in g], pk, sptr)
+        pks.append(pk)
+    outs = [torch.zeros(cfg.n_values, dtype=torch.float32, device=dev) for _ in groups]
+    nbytes = ctx.round_scratch_bytes(J, G, cfg.n_values)
+    scratch = dz(nbytes // 8)
+    desc = ctx.make_round(groups, pks, sks, grads, outs, cfg.n_values)
+    torch.cuda.synchronize()
+
+    def new_events():
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+        for e in evs:
+            e.record(stream)                      # creates the underlying hipEvent_t
+        return evs
+
+    for _ in range(args.warmup):
+        ctx.round(desc, scratch, nbytes, None, sptr)
+    torch.cuda.synchronize()
+    step_events = [new_events() for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ctx.round(desc, scratch, nbytes, [e.cuda_event for e in step_events[i]], sptr)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    phase_ms = [sum(ev[i].elapsed_time(ev[i + 1]) for ev in step_events) / args.steps for i in range(4)]
+
+    # correctness of what was timed: the decoded sums equal the fixed-point sums
+    clamp = ((cfg.t - 1) // 2) // cfg.max_group
+    for gi in (0, G - 1):
+        acc = np.zeros(cfg.n_values, dtype=np.int64)
+        for k in groups[gi]:
+            acc += np.clip(np.rint(grads_host[k] * np.float32(2.0 ** cfg.frac_bits)), -clamp, clamp).astype(np.int64)
+        expect = acc.astype(np.float32) * np.float32(2.0 ** -cfg.frac_bits)
+        if not np.array_equal(outs[gi].cpu().numpy(), expect):
+            print("bench.py: decoded result differs from the fixed-point sum", file=sys.stderr)
+            sys.exit(4)
+
+    fresh = J * C_
+    value = fresh / (ms_per_step * 1e-3)
+    S = 16 * L * N                                    # bytes of one ciphertext
+    logn = cfg.log2_n
+    bf_per_transform = (N // 2) * logn
+    # dominant kernel: the fused encode+encrypt kernel (3 L transforms mod q_i + 1 mod t per ciphertext)
+    n_enc_launch = math.ceil(J / 112)
+    enc_ms = phase_ms[0] / n_enc_launch
+    enc_bf = fresh * (3 * L + 1) * bf_per_transform / n_enc_launch
+    enc_mul_rate = enc_bf * MULS_PER_BUTTERFLY / (enc_ms * 1e-3) / 1e12
+    enc_bytes = (fresh * S + fresh * 4 * N) / n_enc_launch
+    # whole round, algorithmic: (4K+1) L transforms per aggregated ciphertext + (K+1) mod-t transforms
+    round_bf = sum(((4 * len(g) + 1) * L + len(g) + 1) for g in groups) * C_ * bf_per_transform
+    round_bytes = sum(S * (3.5 * len(g) + 1.5) for g in groups) * C_
+    result = {
+        "metric": "BFV gradient ciphertexts/sec (encrypt+aggregate+decrypt-share)",
+        "value": value, "unit": "fresh ciphertexts/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u64", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: N={N}, L={L}, t={cfg.t}, P={P}, G={G}, K={cfg.max_group}, C={C_}, "
+                               f"{cfg.n_values} floats/party", "fresh_ciphertexts": fresh,
+                   "aggregated_ciphertexts": G * C_},
+        "aggregated_ct_per_s": G * C_ / (ms_per_step * 1e-3),
+        "phase_ms": {"encode_encrypt": phase_ms[0], "aggregate": phase_ms[1], "shares": phase_ms[2],
+                     "combine_decode": phase_ms[3]},
+        "round_algorithmic": {"GB": round_bytes / 1e9, "GB_per_s": round_bytes / 1e9 / (ms_per_step * 1e-3),
+                              "frac_hbm_peak": round_bytes / 1e9 / (ms_per_step * 1e-3) / HBM_PEAK_GBS,
+                              "Tmul_per_s": round_bf * MULS_PER_BUTTERFLY / (ms_per_step * 1e-3) / 1e12,
+                              "frac_valu_peak": round_bf * MULS_PER_BUTTERFLY / (ms_per_step * 1e-3) / 1e12 / VALU_PEAK_TOPS},
+        "roofline": {"kernel": "k_encrypt (fused encode + encrypt)", "bound": "alu", "achieved": enc_mul_rate,
+                     "peak": VALU_PEAK_TOPS, "unit": "T 32-bit multiplies/s", "frac": enc_mul_rate / VALU_PEAK_TOPS,
+                     "traffic": None, "avg_launch_ms": enc_ms,
+                     "hbm_algorithmic_GB_per_s": enc_bytes / 1e9 / (enc_ms * 1e-3),
+                     "hbm_frac": enc_bytes / 1e9 / (enc_ms * 1e-3) / HBM_PEAK_GBS},
+    }
+
+    # ---- transform micro-benchmark: forward + inverse, N = 65536, 16 limbs, batch 64 ------
+    if not args.no_ntt:
+        c5 = CONFIGS["C5"]
+        nctx = binding.Context(c5.log2_n, c5.q, 0, seed=c5.seed, alloc=lambda n: dz(n // 8 + 2))
+        polys = dz(c5.batch * c5.L * c5.N)
+        nctx.bench_polys(polys, c5.batch, sptr)
+        ref = polys.clone()
+        for _ in range(3):
+            nctx.ntt_forward(polys, c5.batch, sptr)
+            nctx.ntt_inverse(polys, c5.batch, sptr)
+        reps = 20
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        tf = ti = 0.0
+        for _ in range(reps):
+            e[0].record(stream)
+            nctx.ntt_forward(polys, c5.batch, sptr)
+            e[1].record(stream)
+            nctx.ntt_inverse(polys, c5.batch, sptr)
+            e[2].record(stream)
+            torch.cuda.synchronize()
+            tf += e[0].elapsed_time(e[1])
+            ti += e[1].elapsed_time(e[2])
+        ok = bool(torch.equal(polys, ref))
+        tf, ti = tf / reps, ti / reps
+        nbytes_alg = 2 * c5.batch * c5.L * c5.N * 16
+        bf = 2 * c5.batch * c5.L * (c5.N // 2) * c5.log2_n
+        result["ntt"] = {"workload": "C5: forward+inverse, N=65536, 16 x 60-bit primes, batch 64",
+                         "roundtrip_ok": ok, "forward_ms": tf, "inverse_ms": ti,
+                         "algorithmic_GB": nbytes_alg / 1e9,
+                         "algorithmic_GB_per_s": nbytes_alg / 1e9 / ((tf + ti) * 1e-3),
+                         "frac_hbm_peak": nbytes_alg / 1e9 / ((tf + ti) * 1e-3) / HBM_PEAK_GBS,
+                         "Tmul_per_s": bf * MULS_PER_BUTTERFLY / ((tf + ti) * 1e-3) / 1e12,
+                         "frac_valu_peak": bf * MULS_PER_BUTTERFLY / ((tf + ti) * 1e-3) / 1e12 / VALU_PEAK_TOPS}
+        nctx.close()
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload ---
+    if not args.no_cpu:
+        from oracle import oracle
+        orc = oracle.Oracle(cfg.log2_n, cfg.q, cfg.t, cfg.eta, cfg.frac_bits, cfg.max_group, cfg.seed)
+        okeys = {}
+        sample_groups = list(range(min(G, 2)))
+        for gi in sample_groups:
+            for k in groups[gi]:
+                if k not in okeys:
+                    okeys[k] = orc.keygen_share(k)
+        opks = [orc.aggregate_pk([okeys[k][1] for k in groups[gi]]) for gi in sample_groups]
+        c_end = min(C_, max(1, int(25 * 4096 * 3 / (N * L))))      # about 10-30 s of CPU work
+        t0 = time.perf_counter()
+        threads = 1
+        for gi in sample_groups:
+            res, threads = orc.round_group(opks[gi], [okeys[k][0] for k in groups[gi]],
+                                           [grads_host[k] for k in groups[gi]], groups[gi], gi, 0, c_end)
+            got = outs[gi].cpu().numpy()[: c_end * N]
+            if not np.array_equal(res[: c_end * N][: got.size], got[: res.size]):
+                print("bench.py: GPU result differs from the oracle", file=sys.stderr)
+                sys.exit(5)
+        dt = time.perf_counter() - t0
+        n_fresh = sum(len(groups[gi]) for gi in sample_groups) * c_end
+        result["cpu_baseline"] = {"value": n_fresh / dt, "unit": "fresh ciphertexts/s", "cores": threads,
+                                  "kind": "oracle", "seconds": dt,
+                                  "sample": f"groups {sample_groups}, ciphertext indices 0..{c_end - 1} of {cfg.name} "
+                                            f"({n_fresh} fresh ciphertexts), whole round incl. decode"}
+    ctx.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

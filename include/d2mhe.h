@@ -136,15 +136,39 @@ d2mhe_status d2mhe_combine(d2mhe_ctx *ctx, const uint64_t *ct, const uint64_t *c
 d2mhe_status d2mhe_decode(d2mhe_ctx *ctx, const uint64_t *pt, uint32_t C, uint64_t n_values,
                           float *out, void *stream);
 
-/* ---- fused round for one group (same results as the calls above) ---------------------------- */
-/* Scratch bytes needed by d2mhe_round_group for K members and n_values gradient entries. */
-size_t d2mhe_round_scratch_bytes(const d2mhe_ctx *ctx, uint32_t K, uint64_t n_values);
-/* Every member encodes + encrypts its gradient under pk, the ciphertexts are summed, every
- * member produces a decryption share, the shares are combined and decoded into out_sum
- * [n_values] (the sum of the members' fixed-point gradients).
- * sk_shares, grads: HOST arrays of K device pointers; members: HOST array of K party ids.
- * scratch: device memory; after the call it holds, in this order, the K*C fresh
- * ciphertexts [K][C][2][L][N], the aggregate [C][2][L][N] and the shares [K][C][L][N].    */
+/* ---- fused round (same results as the calls above) ---------------------------------------------- */
+/* One exchange round of Alg. 2 (lines 6-9) for every group at once.  Group g has members
+ * members[group_offsets[g] .. group_offsets[g+1]) (party ids); a (party, group) pair is a
+ * "job".  All arrays of this struct are HOST memory; the pointers they hold are device
+ * pointers.                                                                                */
+typedef struct {
+    uint32_t num_groups;             /* G >= 1                                              */
+    const uint32_t *group_offsets;   /* [G+1], group_offsets[0] = 0, strictly increasing    */
+    const uint32_t *members;         /* [group_offsets[G]] party ids                        */
+    const uint32_t *group_ids;       /* [G] ids used in the Philox counter, NULL = 0..G-1   */
+    const uint64_t *const *pks;      /* [G] prepared public key of each group               */
+    uint32_t num_parties;            /* P: size of the two tables below                     */
+    const uint64_t *const *sk_shares;/* [P] prepared secret share by party id               */
+    const float *const *grads;       /* [P] gradient by party id, n_values floats each      */
+    float *const *out_sums;          /* [G] result per group, n_values floats each          */
+    uint64_t n_values;
+} d2mhe_round_desc;
+
+/* Scratch bytes for a round with num_jobs (party, group) pairs in num_groups groups.      */
+size_t d2mhe_round_scratch_bytes(const d2mhe_ctx *ctx, uint32_t num_jobs, uint32_t num_groups,
+                                 uint64_t n_values);
+/* Every member of every group encodes + encrypts its gradient under the group's key
+ * (ciphertext index c = 0..C-1), the ciphertexts of a group are summed, every member
+ * produces a decryption share of its group's aggregate, and the shares are combined and
+ * decoded into out_sums[g] (the sum of the members' fixed-point gradients).
+ * After the call the scratch holds, in this order, the fresh ciphertexts [J][C][2][L][N]
+ * (job order), the aggregates [G][C][2][L][N] and the shares [J][C][L][N].
+ * phase_events: NULL, or a HOST array of 5 hipEvent_t recorded on `stream` before the
+ * first kernel and after the encrypt, sum, share and combine phases.                       */
+d2mhe_status d2mhe_round(d2mhe_ctx *ctx, const d2mhe_round_desc *desc, void *scratch,
+                         size_t scratch_bytes, void *const *phase_events, void *stream);
+/* The same for a single group: sk_shares, grads: HOST arrays of K device pointers in member
+ * order; members: HOST array of K party ids; scratch as for num_jobs = K, num_groups = 1.   */
 d2mhe_status d2mhe_round_group(d2mhe_ctx *ctx, const uint64_t *pk,
                                const uint64_t *const *sk_shares, const float *const *grads,
                                const uint32_t *members, uint32_t K, uint32_t group,

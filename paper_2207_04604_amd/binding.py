@@ -21,7 +21,7 @@ SYMBOLS = [
     "d2mhe_ntt_index_map", "d2mhe_root", "d2mhe_ntt_forward", "d2mhe_ntt_inverse", "d2mhe_bench_polys",
     "d2mhe_keygen_share", "d2mhe_aggregate_pk", "d2mhe_encode", "d2mhe_encrypt", "d2mhe_add",
     "d2mhe_partial_decrypt", "d2mhe_combine", "d2mhe_decode", "d2mhe_round_scratch_bytes",
-    "d2mhe_round_group",
+    "d2mhe_round", "d2mhe_round_group",
 ]
 
 
@@ -29,6 +29,14 @@ class Params(C.Structure):
     _fields_ = [("log2_n", C.c_uint32), ("num_limbs", C.c_uint32), ("q", C.POINTER(C.c_uint64)),
                 ("t", C.c_uint64), ("cbd_eta", C.c_uint32), ("frac_bits", C.c_uint32),
                 ("max_group", C.c_uint32), ("seed", C.c_uint64)]
+
+
+class RoundDesc(C.Structure):
+    _fields_ = [("num_groups", C.c_uint32), ("group_offsets", C.POINTER(C.c_uint32)),
+                ("members", C.POINTER(C.c_uint32)), ("group_ids", C.POINTER(C.c_uint32)),
+                ("pks", C.POINTER(C.c_void_p)), ("num_parties", C.c_uint32),
+                ("sk_shares", C.POINTER(C.c_void_p)), ("grads", C.POINTER(C.c_void_p)),
+                ("out_sums", C.POINTER(C.c_void_p)), ("n_values", C.c_uint64)]
 
 
 class D2mheError(RuntimeError):
@@ -69,7 +77,8 @@ def lib():
         "d2mhe_partial_decrypt": (i32, [vp, vp, vp, u32, u32, u32, u32, vp, vp]),
         "d2mhe_combine": (i32, [vp, vp, vp, u32, u32, vp, vp]),
         "d2mhe_decode": (i32, [vp, vp, u32, u64, vp, vp]),
-        "d2mhe_round_scratch_bytes": (sz, [vp, u32, u64]),
+        "d2mhe_round_scratch_bytes": (sz, [vp, u32, u32, u64]),
+        "d2mhe_round": (i32, [vp, C.POINTER(RoundDesc), vp, sz, vp, vp]),
         "d2mhe_round_group": (i32, [vp, vp, vp, vp, vp, u32, u32, u64, vp, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
@@ -194,8 +203,39 @@ class Context:
     def decode(self, pt, C_, n_values, out, stream=None):
         _check(lib().d2mhe_decode(self._h, _ptr(pt), C_, n_values, _ptr(out), stream), "d2mhe_decode")
 
-    def round_scratch_bytes(self, K, n_values):
-        return lib().d2mhe_round_scratch_bytes(self._h, K, n_values)
+    def round_scratch_bytes(self, num_jobs, num_groups, n_values):
+        return lib().d2mhe_round_scratch_bytes(self._h, num_jobs, num_groups, n_values)
+
+    def make_round(self, groups, pks, sk_shares, grads, out_sums, n_values, group_ids=None):
+        """Marshal a whole-round description once (host tables); returns an opaque object for round().
+        groups: list of member lists; pks/out_sums: one buffer per group; sk_shares/grads: by party id
+        (list, or dict for sparse ids)."""
+        flat = [int(m) for g in groups for m in g]
+        offs = [0]
+        for g in groups:
+            offs.append(offs[-1] + len(g))
+        P = max(flat) + 1
+        get = (lambda tbl, k: tbl.get(k)) if isinstance(sk_shares, dict) else (lambda tbl, k: tbl[k] if k < len(tbl) else None)
+        keep = {
+            "offs": (C.c_uint32 * len(offs))(*offs),
+            "members": (C.c_uint32 * len(flat))(*flat),
+            "gids": (C.c_uint32 * len(groups))(*group_ids) if group_ids is not None else None,
+            "pks": _ptr_table(pks),
+            "sks": (C.c_void_p * P)(*[_ptr(get(sk_shares, k)) for k in range(P)]),
+            "grads": (C.c_void_p * P)(*[_ptr(get(grads, k)) for k in range(P)]),
+            "outs": _ptr_table(out_sums),
+        }
+        d = RoundDesc(len(groups), keep["offs"], keep["members"], keep["gids"],
+                      C.cast(keep["pks"], C.POINTER(C.c_void_p)), P,
+                      C.cast(keep["sks"], C.POINTER(C.c_void_p)), C.cast(keep["grads"], C.POINTER(C.c_void_p)),
+                      C.cast(keep["outs"], C.POINTER(C.c_void_p)), n_values)
+        d._keep = keep
+        d.num_jobs = len(flat)
+        return d
+
+    def round(self, desc, scratch, scratch_bytes, phase_events=None, stream=None):
+        ev = (C.c_void_p * 5)(*phase_events) if phase_events is not None else None
+        _check(lib().d2mhe_round(self._h, C.byref(desc), _ptr(scratch), scratch_bytes, ev, stream), "d2mhe_round")
 
     def round_group(self, pk, sk_shares, grads, members, group, n_values, out_sum, scratch, scratch_bytes,
                     stream=None):

@@ -42,16 +42,15 @@ struct EngineOps {
     d2mhe_status (*keygen)(d2mhe_ctx *, uint32_t party, uint64_t *sk, uint64_t *pk0, hipStream_t);
     d2mhe_status (*encode)(d2mhe_ctx *, const float *grad, uint64_t n_values, uint64_t *pt, uint32_t C, hipStream_t);
     d2mhe_status (*decode)(d2mhe_ctx *, const uint64_t *pt, uint32_t C, uint64_t n_values, float *out, hipStream_t);
-    // from_float: src holds gradients (encoded on the fly), otherwise plaintext polynomials
-    d2mhe_status (*encrypt)(d2mhe_ctx *, bool from_float, const uint64_t *pk, const PtrList &src, const IdList &ids,
-                            uint32_t members, uint32_t group, uint32_t ct_base, uint64_t n_values, uint64_t *ct,
-                            uint32_t C, hipStream_t);
-    d2mhe_status (*share)(d2mhe_ctx *, const PtrList &sks, const IdList &ids, uint32_t members, uint32_t group,
-                          uint32_t ct_base, const uint64_t *ct, uint64_t *shares, size_t share_stride, uint32_t C,
+    // from_float: jobs.src holds gradients (encoded on the fly), otherwise plaintext polynomials
+    d2mhe_status (*encrypt)(d2mhe_ctx *, bool from_float, const EncJobs &jobs, uint32_t njobs, uint32_t ct_base,
+                            uint64_t n_values, uint32_t C, hipStream_t);
+    d2mhe_status (*share)(d2mhe_ctx *, const ShareJobs &jobs, uint32_t njobs, uint32_t ct_base, uint32_t C,
                           hipStream_t);
-    // out != nullptr: decode to floats; otherwise store the plaintext polynomials in pt
     d2mhe_status (*combine)(d2mhe_ctx *, const uint64_t *ct, const PtrList &shares, uint32_t K, uint32_t C,
-                            uint64_t *pt, float *out, uint64_t n_values, hipStream_t);
+                            uint64_t *pt, hipStream_t);
+    d2mhe_status (*combine_decode)(d2mhe_ctx *, const GroupJobs &jobs, uint32_t njobs, size_t stride, uint32_t C,
+                                   uint64_t n_values, hipStream_t);
 };
 
 const EngineOps *ops_10();

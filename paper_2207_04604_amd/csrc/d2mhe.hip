@@ -408,11 +408,13 @@ d2mhe_status d2mhe_encrypt(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_t *p
     if (misaligned(pk) || misaligned(pt) || misaligned(ct)) return D2MHE_ERR_ALIGN;
     if (party > 0xffffu || group > 0xffffu || (uint64_t)ct_base + C > 0xffffffffull) return D2MHE_ERR_RANGE;
     if (C == 0) return D2MHE_OK;
-    PtrList src;
-    IdList ids;
-    src.p[0] = pt;
-    ids.v[0] = party;
-    return engine_ops(ctx->log2n)->encrypt(ctx, false, pk, src, ids, 1, group, ct_base, 0, ct, C, (hipStream_t)stream);
+    EncJobs jobs;
+    jobs.src[0] = pt;
+    jobs.pk[0] = pk;
+    jobs.out[0] = ct;
+    jobs.party[0] = party;
+    jobs.group[0] = group;
+    return engine_ops(ctx->log2n)->encrypt(ctx, false, jobs, 1, ct_base, 0, C, (hipStream_t)stream);
 }
 
 d2mhe_status d2mhe_add(d2mhe_ctx *ctx, uint64_t *ct_acc, const uint64_t *ct_in, uint32_t C, void *stream)
@@ -439,11 +441,13 @@ d2mhe_status d2mhe_partial_decrypt(d2mhe_ctx *ctx, const uint64_t *sk_share, con
     if (misaligned(sk_share) || misaligned(ct) || misaligned(share)) return D2MHE_ERR_ALIGN;
     if (party > 0xffffu || group > 0xffffu || (uint64_t)ct_base + C > 0xffffffffull) return D2MHE_ERR_RANGE;
     if (C == 0) return D2MHE_OK;
-    PtrList sks;
-    IdList ids;
-    sks.p[0] = sk_share;
-    ids.v[0] = party;
-    return engine_ops(ctx->log2n)->share(ctx, sks, ids, 1, group, ct_base, ct, share, 0, C, (hipStream_t)stream);
+    ShareJobs jobs;
+    jobs.sk[0] = sk_share;
+    jobs.ct[0] = ct;
+    jobs.out[0] = share;
+    jobs.party[0] = party;
+    jobs.group[0] = group;
+    return engine_ops(ctx->log2n)->share(ctx, jobs, 1, ct_base, C, (hipStream_t)stream);
 }
 
 d2mhe_status d2mhe_combine(d2mhe_ctx *ctx, const uint64_t *ct, const uint64_t *const *shares, uint32_t K, uint32_t C,
@@ -460,16 +464,138 @@ d2mhe_status d2mhe_combine(d2mhe_ctx *ctx, const uint64_t *ct, const uint64_t *c
         sh.p[k] = shares[k];
     }
     if (C == 0) return D2MHE_OK;
-    return engine_ops(ctx->log2n)->combine(ctx, ct, sh, K, C, pt, nullptr, 0, (hipStream_t)stream);
+    return engine_ops(ctx->log2n)->combine(ctx, ct, sh, K, C, pt, (hipStream_t)stream);
 }
 
-size_t d2mhe_round_scratch_bytes(const d2mhe_ctx *ctx, uint32_t K, uint64_t n_values)
+namespace {
+
+// words of scratch for J (party, group) jobs, G groups, C ciphertext indices
+size_t round_words(const d2mhe_ctx *ctx, uint64_t J, uint64_t G, uint64_t C)
 {
-    if (!ctx || !ctx->t || K == 0) return 0;
+    const size_t LN = (size_t)ctx->L * ctx->N;
+    return (size_t)C * ((size_t)J * 2 * LN + (size_t)G * 2 * LN + (size_t)J * LN);
+}
+
+}  // namespace
+
+size_t d2mhe_round_scratch_bytes(const d2mhe_ctx *ctx, uint32_t num_jobs, uint32_t num_groups, uint64_t n_values)
+{
+    if (!ctx || !ctx->t || num_jobs == 0 || num_groups == 0) return 0;
     const uint64_t C = (n_values + ctx->N - 1) / ctx->N;
-    const size_t LN = (size_t)ctx->L * ctx->N * sizeof(uint64_t);
-    // K*C fresh ciphertexts, one aggregate per index, K*C shares
-    return (size_t)C * ((size_t)K * 2 * LN + 2 * LN + (size_t)K * LN);
+    return round_words(ctx, num_jobs, num_groups, C) * sizeof(uint64_t);
+}
+
+d2mhe_status d2mhe_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, void *scratch, size_t scratch_bytes,
+                         void *const *phase_events, void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!d || !scratch) return D2MHE_ERR_NULL;
+    if (!d->group_offsets || !d->members || !d->pks || !d->sk_shares || !d->grads || !d->out_sums)
+        return D2MHE_ERR_NULL;
+    const uint32_t G = d->num_groups;
+    if (G == 0 || G > 0xffffu) return D2MHE_ERR_RANGE;
+    if (d->group_offsets[0] != 0) return D2MHE_ERR_RANGE;
+    const uint32_t J = d->group_offsets[G];
+    for (uint32_t g = 0; g < G; ++g) {
+        if (d->group_offsets[g + 1] <= d->group_offsets[g]) return D2MHE_ERR_RANGE;
+        const uint32_t K = d->group_offsets[g + 1] - d->group_offsets[g];
+        if (K > (uint32_t)MAX_GROUP || K > ctx->max_group) return D2MHE_ERR_RANGE;
+        if (!d->pks[g] || !d->out_sums[g]) return D2MHE_ERR_NULL;
+        if (misaligned(d->pks[g]) || misaligned(d->out_sums[g])) return D2MHE_ERR_ALIGN;
+    }
+    for (uint32_t j = 0; j < J; ++j) {
+        const uint32_t party = d->members[j];
+        if (party >= d->num_parties || party > 0xffffu) return D2MHE_ERR_RANGE;
+        if (!d->sk_shares[party] || !d->grads[party]) return D2MHE_ERR_NULL;
+        if (misaligned(d->sk_shares[party]) || misaligned(d->grads[party])) return D2MHE_ERR_ALIGN;
+    }
+    if (misaligned(scratch)) return D2MHE_ERR_ALIGN;
+    if (d->n_values == 0) return D2MHE_OK;
+    const uint64_t C64 = (d->n_values + ctx->N - 1) / ctx->N;
+    if (C64 > 0x7fffffffull) return D2MHE_ERR_RANGE;
+    const uint32_t C = (uint32_t)C64;
+    if (scratch_bytes < round_words(ctx, J, G, C) * sizeof(uint64_t)) return D2MHE_ERR_WORKSPACE;
+
+    const size_t LN = (size_t)ctx->L * ctx->N;
+    const size_t ct_words = (size_t)C * 2 * LN, sh_words = (size_t)C * LN;
+    uint64_t *cts = (uint64_t *)scratch;
+    uint64_t *agg = cts + (size_t)J * ct_words;
+    uint64_t *shares = agg + (size_t)G * ct_words;
+    hipStream_t st = (hipStream_t)stream;
+    const EngineOps *ops = engine_ops(ctx->log2n);
+    hipEvent_t *ev = (hipEvent_t *)phase_events;
+    if (ev) D2_HIP(ctx, hipEventRecord(ev[0], st));
+
+    // phase 1: every member of every group encodes and encrypts its gradient
+    std::vector<uint32_t> group_of(J);
+    for (uint32_t g = 0; g < G; ++g)
+        for (uint32_t j = d->group_offsets[g]; j < d->group_offsets[g + 1]; ++j) group_of[j] = g;
+    for (uint32_t j0 = 0; j0 < J; j0 += JOB_CHUNK) {
+        const uint32_t n = J - j0 < (uint32_t)JOB_CHUNK ? J - j0 : (uint32_t)JOB_CHUNK;
+        EncJobs jobs;
+        for (uint32_t i = 0; i < n; ++i) {
+            const uint32_t j = j0 + i, g = group_of[j];
+            jobs.src[i] = d->grads[d->members[j]];
+            jobs.pk[i] = d->pks[g];
+            jobs.out[i] = cts + (size_t)j * ct_words;
+            jobs.party[i] = d->members[j];
+            jobs.group[i] = d->group_ids ? d->group_ids[g] : g;
+        }
+        d2mhe_status s = ops->encrypt(ctx, true, jobs, n, 0, d->n_values, C, st);
+        if (s != D2MHE_OK) return s;
+    }
+    if (ev) D2_HIP(ctx, hipEventRecord(ev[1], st));
+
+    // phase 2: homomorphic sum per group
+    for (uint32_t g0 = 0; g0 < G; g0 += JOB_CHUNK) {
+        const uint32_t n = G - g0 < (uint32_t)JOB_CHUNK ? G - g0 : (uint32_t)JOB_CHUNK;
+        GroupJobs jobs;
+        for (uint32_t i = 0; i < n; ++i) {
+            const uint32_t g = g0 + i;
+            jobs.first[i] = cts + (size_t)d->group_offsets[g] * ct_words;
+            jobs.ct[i] = nullptr;
+            jobs.out[i] = agg + (size_t)g * ct_words;
+            jobs.K[i] = d->group_offsets[g + 1] - d->group_offsets[g];
+        }
+        hipLaunchKernelGGL(k_sum_groups, dim3((unsigned)((ct_words / 2 + 255) / 256), n), dim3(256), 0, st, jobs,
+                           ct_words, ctx->d_tabs, ctx->L, ctx->log2n, ct_words);
+        D2_LAUNCHED(ctx);
+    }
+    if (ev) D2_HIP(ctx, hipEventRecord(ev[2], st));
+
+    // phase 3: every member's decryption share of its group's aggregate
+    for (uint32_t j0 = 0; j0 < J; j0 += JOB_CHUNK) {
+        const uint32_t n = J - j0 < (uint32_t)JOB_CHUNK ? J - j0 : (uint32_t)JOB_CHUNK;
+        ShareJobs jobs;
+        for (uint32_t i = 0; i < n; ++i) {
+            const uint32_t j = j0 + i, g = group_of[j];
+            jobs.sk[i] = d->sk_shares[d->members[j]];
+            jobs.ct[i] = agg + (size_t)g * ct_words;
+            jobs.out[i] = shares + (size_t)j * sh_words;
+            jobs.party[i] = d->members[j];
+            jobs.group[i] = d->group_ids ? d->group_ids[g] : g;
+        }
+        d2mhe_status s = ops->share(ctx, jobs, n, 0, C, st);
+        if (s != D2MHE_OK) return s;
+    }
+    if (ev) D2_HIP(ctx, hipEventRecord(ev[3], st));
+
+    // phase 4: combine the shares, round, decode
+    for (uint32_t g0 = 0; g0 < G; g0 += JOB_CHUNK) {
+        const uint32_t n = G - g0 < (uint32_t)JOB_CHUNK ? G - g0 : (uint32_t)JOB_CHUNK;
+        GroupJobs jobs;
+        for (uint32_t i = 0; i < n; ++i) {
+            const uint32_t g = g0 + i;
+            jobs.first[i] = shares + (size_t)d->group_offsets[g] * sh_words;
+            jobs.ct[i] = agg + (size_t)g * ct_words;
+            jobs.out[i] = d->out_sums[g];
+            jobs.K[i] = d->group_offsets[g + 1] - d->group_offsets[g];
+        }
+        d2mhe_status s = ops->combine_decode(ctx, jobs, n, sh_words, C, d->n_values, st);
+        if (s != D2MHE_OK) return s;
+    }
+    if (ev) D2_HIP(ctx, hipEventRecord(ev[4], st));
+    return D2MHE_OK;
 }
 
 d2mhe_status d2mhe_round_group(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_t *const *sk_shares,
@@ -479,40 +605,31 @@ d2mhe_status d2mhe_round_group(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_
     D2_NEED_SCHEME(ctx);
     if (!pk || !sk_shares || !grads || !members || !out_sum || !scratch) return D2MHE_ERR_NULL;
     if (K == 0 || K > (uint32_t)MAX_GROUP || K > ctx->max_group || group > 0xffffu) return D2MHE_ERR_RANGE;
-    if (n_values == 0) return D2MHE_OK;
-    const uint64_t C64 = (n_values + ctx->N - 1) / ctx->N;
-    if (C64 > 0x7fffffffull) return D2MHE_ERR_RANGE;
-    if (scratch_bytes < d2mhe_round_scratch_bytes(ctx, K, n_values)) return D2MHE_ERR_WORKSPACE;
-    if (misaligned(pk) || misaligned(out_sum) || misaligned(scratch)) return D2MHE_ERR_ALIGN;
-    const uint32_t C = (uint32_t)C64;
-    PtrList gl, sl, cl;
-    IdList ids;
-    const size_t LN = (size_t)ctx->L * ctx->N;
-    uint64_t *cts = (uint64_t *)scratch;
-    uint64_t *agg = cts + (size_t)K * C * 2 * LN;
-    uint64_t *shares = agg + (size_t)C * 2 * LN;
-    for (uint32_t k = 0; k < K; ++k) {
-        if (!sk_shares[k] || !grads[k]) return D2MHE_ERR_NULL;
-        if (misaligned(sk_shares[k]) || misaligned(grads[k])) return D2MHE_ERR_ALIGN;
+    // a one-group round
+    uint32_t offsets[2] = {0, K};
+    for (uint32_t k = 0; k < K; ++k)
         if (members[k] > 0xffffu) return D2MHE_ERR_RANGE;
-        gl.p[k] = grads[k];
-        sl.p[k] = sk_shares[k];
-        cl.p[k] = cts + (size_t)k * C * 2 * LN;
-        ids.v[k] = members[k];
+    // pointer tables indexed by party id: build sparse views of size max id + 1
+    uint32_t max_id = 0;
+    for (uint32_t k = 0; k < K; ++k) max_id = members[k] > max_id ? members[k] : max_id;
+    std::vector<const uint64_t *> sk_by_party(max_id + 1, nullptr);
+    std::vector<const float *> grad_by_party(max_id + 1, nullptr);
+    for (uint32_t k = 0; k < K; ++k) {
+        sk_by_party[members[k]] = sk_shares[k];
+        grad_by_party[members[k]] = grads[k];
     }
-    hipStream_t st = (hipStream_t)stream;
-    const EngineOps *ops = engine_ops(ctx->log2n);
-    d2mhe_status s = ops->encrypt(ctx, true, pk, gl, ids, K, group, 0, n_values, cts, C, st);
-    if (s != D2MHE_OK) return s;
-    const size_t total = (size_t)C * 2 * LN;
-    hipLaunchKernelGGL(k_sum, dim3((unsigned)((total / 2 + 255) / 256)), dim3(256), 0, st, agg, cl, K, ctx->d_tabs,
-                       ctx->L, ctx->log2n, total);
-    D2_LAUNCHED(ctx);
-    s = ops->share(ctx, sl, ids, K, group, 0, agg, shares, (size_t)C * LN, C, st);
-    if (s != D2MHE_OK) return s;
-    PtrList hl;
-    for (uint32_t k = 0; k < K; ++k) hl.p[k] = shares + (size_t)k * C * LN;
-    return ops->combine(ctx, agg, hl, K, C, nullptr, out_sum, n_values, st);
+    d2mhe_round_desc d;
+    d.num_groups = 1;
+    d.group_offsets = offsets;
+    d.members = members;
+    d.group_ids = &group;
+    d.pks = &pk;
+    d.num_parties = max_id + 1;
+    d.sk_shares = sk_by_party.data();
+    d.grads = grad_by_party.data();
+    d.out_sums = &out_sum;
+    d.n_values = n_values;
+    return d2mhe_round(ctx, &d, scratch, scratch_bytes, nullptr, stream);
 }
 
 }  // extern "C"

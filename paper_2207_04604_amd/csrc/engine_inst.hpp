@@ -57,39 +57,40 @@ struct Launch {
         return D2MHE_OK;
     }
 
-    static d2mhe_status encrypt(d2mhe_ctx *ctx, bool from_float, const uint64_t *pk, const PtrList &src,
-                                const IdList &ids, uint32_t members, uint32_t group, uint32_t ct_base,
-                                uint64_t n_values, uint64_t *ct, uint32_t C, hipStream_t st)
+    static d2mhe_status encrypt(d2mhe_ctx *ctx, bool from_float, const EncJobs &jobs, uint32_t njobs,
+                                uint32_t ct_base, uint64_t n_values, uint32_t C, hipStream_t st)
     {
         if (from_float)
-            hipLaunchKernelGGL((k_encrypt<ENG, true>), dim3(C, members), dim3(ENG::T), 0, st, pk, src, ids, group,
-                               ct_base, n_values, ct, C, ctx->d_tabs, ctx->rc);
+            hipLaunchKernelGGL((k_encrypt<ENG, true>), dim3(C, njobs), dim3(ENG::T), 0, st, jobs, ct_base, n_values,
+                               ctx->d_tabs, ctx->rc);
         else
-            hipLaunchKernelGGL((k_encrypt<ENG, false>), dim3(C, members), dim3(ENG::T), 0, st, pk, src, ids, group,
-                               ct_base, n_values, ct, C, ctx->d_tabs, ctx->rc);
+            hipLaunchKernelGGL((k_encrypt<ENG, false>), dim3(C, njobs), dim3(ENG::T), 0, st, jobs, ct_base, n_values,
+                               ctx->d_tabs, ctx->rc);
         D2_LAUNCHED(ctx);
         return D2MHE_OK;
     }
 
-    static d2mhe_status share(d2mhe_ctx *ctx, const PtrList &sks, const IdList &ids, uint32_t members, uint32_t group,
-                              uint32_t ct_base, const uint64_t *ct, uint64_t *shares, size_t share_stride, uint32_t C,
+    static d2mhe_status share(d2mhe_ctx *ctx, const ShareJobs &jobs, uint32_t njobs, uint32_t ct_base, uint32_t C,
                               hipStream_t st)
     {
-        hipLaunchKernelGGL(k_share<ENG>, dim3(C, members), dim3(ENG::T), 0, st, sks, ids, group, ct_base, ct, shares,
-                           share_stride, ctx->d_tabs, ctx->rc);
+        hipLaunchKernelGGL(k_share<ENG>, dim3(C, njobs), dim3(ENG::T), 0, st, jobs, ct_base, ctx->d_tabs, ctx->rc);
         D2_LAUNCHED(ctx);
         return D2MHE_OK;
     }
 
     static d2mhe_status combine(d2mhe_ctx *ctx, const uint64_t *ct, const PtrList &shares, uint32_t K, uint32_t C,
-                                uint64_t *pt, float *out, uint64_t n_values, hipStream_t st)
+                                uint64_t *pt, hipStream_t st)
     {
-        if (out)
-            hipLaunchKernelGGL((k_combine<ENG, true>), dim3(C), dim3(ENG::T), 0, st, ct, shares, K, pt, out, n_values,
-                               ctx->d_tabs, ctx->rc);
-        else
-            hipLaunchKernelGGL((k_combine<ENG, false>), dim3(C), dim3(ENG::T), 0, st, ct, shares, K, pt, out,
-                               n_values, ctx->d_tabs, ctx->rc);
+        hipLaunchKernelGGL(k_combine<ENG>, dim3(C), dim3(ENG::T), 0, st, ct, shares, K, pt, ctx->d_tabs, ctx->rc);
+        D2_LAUNCHED(ctx);
+        return D2MHE_OK;
+    }
+
+    static d2mhe_status combine_decode(d2mhe_ctx *ctx, const GroupJobs &jobs, uint32_t njobs, size_t stride,
+                                       uint32_t C, uint64_t n_values, hipStream_t st)
+    {
+        hipLaunchKernelGGL(k_combine_decode<ENG>, dim3(C, njobs), dim3(ENG::T), 0, st, jobs, stride, n_values,
+                           ctx->d_tabs, ctx->rc);
         D2_LAUNCHED(ctx);
         return D2MHE_OK;
     }
@@ -97,12 +98,13 @@ struct Launch {
     // full set (ring degrees a single workgroup can hold)
     static EngineOps full()
     {
-        return EngineOps{ENG::ELOG, ENG::LOGB, &ntt, &keygen, &encode, &decode, &encrypt, &share, &combine};
+        return EngineOps{ENG::ELOG, ENG::LOGB, &ntt, &keygen, &encode, &decode, &encrypt, &share, &combine,
+                         &combine_decode};
     }
     // transforms only (longer rings)
     static EngineOps transforms_only()
     {
-        return EngineOps{ENG::ELOG, ENG::LOGB, &ntt, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+        return EngineOps{ENG::ELOG, ENG::LOGB, &ntt, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     }
 };
 

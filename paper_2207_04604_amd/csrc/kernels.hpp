@@ -36,8 +36,28 @@ struct RoundConst {
 struct PtrList {
     const void *p[MAX_GROUP];
 };
-struct IdList {
-    uint32_t v[MAX_GROUP];
+
+// Job tables passed by value in the kernel arguments; grid.y indexes the job.
+constexpr int JOB_CHUNK = 112;   // 112 * 32 B of table + the other arguments stay under the 4 KB argument limit
+struct EncJobs {                       // one job = one (party, group) pair encrypting C ciphertexts
+    const void *src[JOB_CHUNK];        // gradient (float) or plaintext polynomials (uint64)
+    const uint64_t *pk[JOB_CHUNK];     // prepared public key of the group
+    uint64_t *out[JOB_CHUNK];          // ciphertexts [C][2][L][N]
+    uint32_t party[JOB_CHUNK];
+    uint32_t group[JOB_CHUNK];
+};
+struct ShareJobs {                     // one job = one member's shares of C aggregated ciphertexts
+    const uint64_t *sk[JOB_CHUNK];     // prepared secret share
+    const uint64_t *ct[JOB_CHUNK];     // aggregate [C][2][L][N]
+    uint64_t *out[JOB_CHUNK];          // shares [C][L][N]
+    uint32_t party[JOB_CHUNK];
+    uint32_t group[JOB_CHUNK];
+};
+struct GroupJobs {                     // one job = one group: K buffers laid out at a fixed stride
+    const uint64_t *first[JOB_CHUNK];  // buffer of the group's first member
+    const uint64_t *ct[JOB_CHUNK];     // aggregate (combine) / unused (sum)
+    void *out[JOB_CHUNK];              // aggregate (sum) / decoded floats (combine)
+    uint32_t K[JOB_CHUNK];
 };
 
 D2_DEV uint32_t bitrev(uint32_t v, int bits) { return __brev(v) >> (32 - bits); }
@@ -350,33 +370,33 @@ __global__ void __launch_bounds__(ENG::T) k_keygen(uint32_t party, uint64_t *sk,
 }
 
 // -------------------------------------------------------------------------------------
-// BFV.Encrypt in evaluation form.  grid = (C, members); one workgroup per ciphertext.
+// BFV.Encrypt in evaluation form.  grid = (C, jobs); one workgroup per ciphertext.
 //   c0 = NTT(Lambda m + e0) + NTT(mu) * p0,   c1 = NTT(e1) + NTT(mu) * p1.
 // FROM_FLOAT: the plaintext is encoded on the fly from the member's gradient;
 // otherwise it is read from pt [C][N].
 // -------------------------------------------------------------------------------------
 template <class ENG, bool FROM_FLOAT>
-__global__ void __launch_bounds__(ENG::T) k_encrypt(const uint64_t *pk, PtrList src, IdList parties, uint32_t group,
-                                                    uint32_t ct_base, uint64_t n_values, uint64_t *ct, uint32_t C,
+__global__ void __launch_bounds__(ENG::T) k_encrypt(EncJobs jobs, uint32_t ct_base, uint64_t n_values,
                                                     const LimbTab *tabs, RoundConst rc)
 {
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     uint32_t *lds32 = (uint32_t *)lds;
     constexpr int E = ENG::E;
     const int tid = threadIdx.x;
-    const uint32_t c = blockIdx.x, member = blockIdx.y, L = rc.L;
-    const uint32_t party = parties.v[member];
+    const uint32_t c = blockIdx.x, job = blockIdx.y, L = rc.L;
+    const uint32_t party = jobs.party[job], group = jobs.group[job];
+    const uint64_t *pk = jobs.pk[job];
     const size_t LN = (size_t)L * ENG::NB;
-    uint64_t *out = ct + ((size_t)member * C + c) * 2 * LN;
+    uint64_t *out = jobs.out[job] + (size_t)c * 2 * LN;
 
     uint32_t m[E];
     {
         uint64_t x[E];
         if (FROM_FLOAT) {
-            encode_to_regs<ENG>(x, lds, tid, (const float *)src.p[member], (uint64_t)c * ENG::NB, n_values,
+            encode_to_regs<ENG>(x, lds, tid, (const float *)jobs.src[job], (uint64_t)c * ENG::NB, n_values,
                                 tabs[L], rc);
         } else {
-            const uint64_t *pt = (const uint64_t *)src.p[member] + (size_t)c * ENG::NB;
+            const uint64_t *pt = (const uint64_t *)jobs.src[job] + (size_t)c * ENG::NB;
 #pragma unroll
             for (int k = 0; k < E; ++k) x[k] = pt[ENG::coef_pos(k, tid)];
         }
@@ -423,25 +443,23 @@ __global__ void __launch_bounds__(ENG::T) k_encrypt(const uint64_t *pk, PtrList 
 }
 
 // -------------------------------------------------------------------------------------
-// Decryption share h = s c1 + e in evaluation form.  grid = (C, members).
-// ct: [C][2][L][N] (the aggregate); share buffer of member m: shares + m * share_stride.
+// Decryption share h = s c1 + e in evaluation form.  grid = (C, jobs).
 // -------------------------------------------------------------------------------------
 template <class ENG>
-__global__ void __launch_bounds__(ENG::T) k_share(PtrList sks, IdList parties, uint32_t group, uint32_t ct_base,
-                                                  const uint64_t *ct, uint64_t *shares, size_t share_stride,
-                                                  const LimbTab *tabs, RoundConst rc)
+__global__ void __launch_bounds__(ENG::T) k_share(ShareJobs jobs, uint32_t ct_base, const LimbTab *tabs, RoundConst rc)
 {
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     uint32_t *lds32 = (uint32_t *)lds;
     constexpr int E = ENG::E;
     const int tid = threadIdx.x;
-    const uint32_t c = blockIdx.x, member = blockIdx.y, L = rc.L;
+    const uint32_t c = blockIdx.x, job = blockIdx.y, L = rc.L;
     const size_t LN = (size_t)L * ENG::NB;
-    const uint64_t *sk = (const uint64_t *)sks.p[member];
-    const uint64_t *c1 = ct + ((size_t)c * 2 + 1) * LN;
-    uint64_t *out = shares + (size_t)member * share_stride + (size_t)c * LN;
+    const uint64_t *sk = jobs.sk[job];
+    const uint64_t *c1 = jobs.ct[job] + ((size_t)c * 2 + 1) * LN;
+    uint64_t *out = jobs.out[job] + (size_t)c * LN;
+    const uint32_t group = jobs.group[job];
     int32_t e[E];
-    stage_cbd<ENG>(lds32, tid, DOM_DEC_E, parties.v[member], group, ct_base + c, rc);
+    stage_cbd<ENG>(lds32, tid, DOM_DEC_E, jobs.party[job], group, ct_base + c, rc);
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < E; ++k) e[k] = (int32_t)lds32[ENG::coef_pos(k, tid)];
@@ -469,11 +487,11 @@ __global__ void __launch_bounds__(ENG::T) k_share(PtrList sks, IdList parties, u
 // than 2^-63, so the rounding is exact unless t y / Q lies within L * 2^-63 of a half-integer).
 // grid = C.  DECODE: continue to floats instead of storing the plaintext polynomial.
 // -------------------------------------------------------------------------------------
-template <class ENG, bool DECODE>
-__global__ void __launch_bounds__(ENG::T) k_combine(const uint64_t *ct, PtrList shares, uint32_t K, uint64_t *pt,
-                                                    float *out, uint64_t n_values, const LimbTab *tabs, RoundConst rc)
+// SH(j) returns the share buffer [C][L][N] of member j.
+template <class ENG, bool DECODE, class SH>
+D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_t K, uint64_t *pt, float *out,
+                         uint64_t n_values, const LimbTab *tabs, const RoundConst &rc)
 {
-    __shared__ uint64_t lds[ENG::LDS_WORDS];
     constexpr int E = ENG::E;
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x, L = rc.L;
@@ -490,7 +508,7 @@ __global__ void __launch_bounds__(ENG::T) k_combine(const uint64_t *ct, PtrList 
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = c0[off + ENG::eval_pos(k, tid)];
         for (uint32_t j = 0; j < K; ++j) {
-            const uint64_t *h = (const uint64_t *)shares.p[j] + (size_t)c * LN + off;
+            const uint64_t *h = share_of(j) + (size_t)c * LN + off;
 #pragma unroll
             for (int k = 0; k < E; ++k) x[k] = add_mod(x[k], h[ENG::eval_pos(k, tid)], q);
         }
@@ -518,6 +536,28 @@ __global__ void __launch_bounds__(ENG::T) k_combine(const uint64_t *ct, PtrList 
 #pragma unroll
         for (int k = 0; k < E; ++k) pt[(size_t)c * ENG::NB + ENG::coef_pos(k, tid)] = m[k];
     }
+}
+
+// one aggregate, K share buffers anywhere in memory, plaintext polynomials out; grid = C
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T) k_combine(const uint64_t *ct, PtrList shares, uint32_t K, uint64_t *pt,
+                                                    const LimbTab *tabs, RoundConst rc)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    combine_body<ENG, false>(lds, ct, [&](uint32_t j) { return (const uint64_t *)shares.p[j]; }, K, pt,
+                             (float *)nullptr, 0, tabs, rc);
+}
+
+// whole round: grid = (C, groups); the group's shares lie `stride` words apart; decoded floats out
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T) k_combine_decode(GroupJobs jobs, size_t stride, uint64_t n_values,
+                                                           const LimbTab *tabs, RoundConst rc)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    const uint32_t job = blockIdx.y;
+    const uint64_t *first = jobs.first[job];
+    combine_body<ENG, true>(lds, jobs.ct[job], [&](uint32_t j) { return first + (size_t)j * stride; }, jobs.K[job],
+                            (uint64_t *)nullptr, (float *)jobs.out[job], n_values, tabs, rc);
 }
 
 }  // namespace d2

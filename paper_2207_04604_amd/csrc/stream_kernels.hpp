@@ -53,4 +53,23 @@ __global__ void __launch_bounds__(256) k_sum(uint64_t *dst, PtrList src, uint32_
     *(ulonglong2 *)(dst + i) = acc;
 }
 
+// Whole round: out[g] = sum of the K_g ciphertext buffers of group g (stride words apart).
+// grid = (ceil(words / 512), groups); `words` = C * 2 * L * N per buffer.
+__global__ void __launch_bounds__(256) k_sum_groups(GroupJobs jobs, size_t stride, const LimbTab *tabs, uint32_t L,
+                                                    uint32_t log2n, size_t words)
+{
+    size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 2;
+    if (i >= words) return;
+    const uint32_t job = blockIdx.y, K = jobs.K[job];
+    const uint64_t *src = jobs.first[job];
+    uint64_t q = tabs[(i >> log2n) % L].q;
+    ulonglong2 acc = *(const ulonglong2 *)(src + i);
+    for (uint32_t k = 1; k < K; ++k) {
+        ulonglong2 v = *(const ulonglong2 *)(src + (size_t)k * stride + i);
+        acc.x = add_mod(acc.x, v.x, q);
+        acc.y = add_mod(acc.y, v.y, q);
+    }
+    *(ulonglong2 *)((uint64_t *)jobs.out[job] + i) = acc;
+}
+
 }  // namespace d2

@@ -124,7 +124,7 @@ def run_calls_and_compare(cfg, o, ctx, perm, keys, members, group, grads, ct_bas
 
 def run_fused(ctx, o, dpk, keys, members, group, grads, n_values):
     K = len(members)
-    nbytes = ctx.round_scratch_bytes(K, n_values)
+    nbytes = ctx.round_scratch_bytes(K, 1, n_values)
     scratch = dzeros(nbytes // 8)
     out = torch.zeros(n_values, dtype=torch.float32, device=DEV)
     dgr = [to_dev(grads[k]) for k in members]
@@ -259,3 +259,77 @@ def test_eta_and_small_prime_variants():
         keys = Keys(o, ctx, perm, [0, 1])
         run_calls_and_compare(cfg, o, ctx, perm, keys, [0, 1], 2, grads)
         ctx.close()
+
+
+# ------------------------------------------------------------------------------------------
+def _setup_whole_round(cfg):
+    o, ctx, perm = make_pair(cfg)
+    groups = cfg.groups()
+    grads = cfg.gradients()
+    keys = Keys(o, ctx, perm, range(cfg.parties), check=False)
+    pks = [keys.group_pk(g, perm, check=False) for g in groups]
+    dgr = [to_dev(g) for g in grads]
+    outs = [torch.zeros(cfg.n_values, dtype=torch.float32, device=DEV) for _ in groups]
+    J = sum(len(g) for g in groups)
+    nbytes = ctx.round_scratch_bytes(J, len(groups), cfg.n_values)
+    scratch = dzeros(nbytes // 8)
+    desc = ctx.make_round(groups, [p[1] for p in pks], [keys.sk[k] for k in range(cfg.parties)], dgr, outs,
+                          cfg.n_values)
+    return o, ctx, perm, groups, grads, keys, pks, outs, scratch, nbytes, desc, J
+
+
+@pytest.mark.parametrize("name,jobs_sample,ct_sample", [("C1", [(0, 0), (0, 3)], (0, 3)),
+                                                       ("C2", [(0, 0), (7, 2), (15, 4)], (0, 13, 24)),
+                                                       ("C3", [(0, 0), (19, 3), (31, 6)], (0, 152))])
+def test_whole_round_in_the_benchmark_launch_shape(name, jobs_sample, ct_sample):
+    """All groups of a configuration in one d2mhe_round call (the launch shape bench.py times),
+    with phase events.  Every group's decoded result is checked against the fixed-point sum;
+    sampled fresh ciphertexts, aggregates and shares are recomputed by the oracle."""
+    cfg = CONFIGS[name]
+    o, ctx, perm, groups, grads, keys, pks, outs, scratch, nbytes, desc, J = _setup_whole_round(cfg)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+    for e in evs:
+        e.record()
+    for rep in range(2):         # twice: the second run overwrites the scratch of the first
+        ctx.round(desc, scratch, nbytes, [e.cuda_event for e in evs], torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert all(evs[i].elapsed_time(evs[i + 1]) > 0 for i in range(4))
+    clamp = o.encode_clamp()
+    for gi, g in enumerate(groups):
+        expect = fixed_point_sum([grads[k] for k in g], cfg.frac_bits, clamp)
+        assert np.array_equal(outs[gi].cpu().numpy(), expect), f"group {gi}"
+    L, N, C_, G = cfg.L, cfg.N, cfg.C, len(groups)
+    LN = L * N
+    offs = np.cumsum([0] + [len(g) for g in groups])
+    cts = scratch[:J * C_ * 2 * LN].view(J, C_, 2 * LN)
+    agg = scratch[J * C_ * 2 * LN:(J + G) * C_ * 2 * LN].view(G, C_, 2 * LN)
+    shares = scratch[(J + G) * C_ * 2 * LN:(J + G) * C_ * 2 * LN + J * C_ * LN].view(J, C_, LN)
+    for (gi, mi) in jobs_sample:
+        g = groups[gi]
+        opk = pks[gi][0]
+        for c in ct_sample:
+            lo, hi = c * N, min((c + 1) * N, cfg.n_values)
+            oagg = None
+            for m, k in enumerate(g):
+                oct_ = o.encrypt(opk, o.encode(grads[k][lo:hi]), k, gi, c)
+                if m == mi:
+                    assert np.array_equal(to_host(cts[offs[gi] + m, c], (1, 2, L, N)), to_eval(o, perm, oct_)), (gi, m, c)
+                oagg = oct_ if oagg is None else o.add(oagg, oct_)
+            assert np.array_equal(to_host(agg[gi, c], (1, 2, L, N)), to_eval(o, perm, oagg)), (gi, c)
+            osh = o.partial_decrypt(keys.osk[g[mi]], oagg, g[mi], gi, c)
+            assert np.array_equal(to_host(shares[offs[gi] + mi, c], (1, L, N)), to_eval(o, perm, osh)), (gi, mi, c)
+    ctx.close()
+
+
+def test_whole_round_argument_checks():
+    cfg = CONFIGS["C1"]
+    o, ctx, perm, groups, grads, keys, pks, outs, scratch, nbytes, desc, J = _setup_whole_round(cfg)
+    with pytest.raises(B.D2mheError) as ei:
+        ctx.round(desc, scratch, nbytes - 8)
+    assert ei.value.status == B.ERR_WORKSPACE
+    bad = ctx.make_round([[0, 1, 2, 3, 0]], [pks[0][1]], [keys.sk[k] for k in range(4)], [to_dev(g) for g in grads],
+                         outs, cfg.n_values)
+    with pytest.raises(B.D2mheError) as ei:           # 5 members > max_group = 4
+        ctx.round(bad, scratch, nbytes * 2)
+    assert ei.value.status == B.ERR_RANGE
+    ctx.close()

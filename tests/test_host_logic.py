@@ -76,7 +76,7 @@ def test_create_argument_checks(lib):
     # entry points refuse a NULL context
     assert lib.d2mhe_ntt_forward(None, fake.ctypes.data, 1, None) == B.ERR_NULL
     assert lib.d2mhe_encrypt(None, None, None, 1, 0, 0, 0, None, None) == B.ERR_NULL
-    assert lib.d2mhe_round_scratch_bytes(None, 4, 4096) == 0
+    assert lib.d2mhe_round_scratch_bytes(None, 4, 1, 4096) == 0
 
 
 def test_workspace_size_formula(lib):
