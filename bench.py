@@ -181,13 +181,13 @@ def main():
         from oracle import oracle
         orc = oracle.Oracle(cfg.log2_n, cfg.q, cfg.t, cfg.eta, cfg.frac_bits, cfg.max_group, cfg.seed)
         okeys = {}
-        sample_groups = list(range(min(G, 2)))
+        sample_groups = list(range(G if cfg.name in ("C1", "C2") else 1))
         for gi in sample_groups:
             for k in groups[gi]:
                 if k not in okeys:
                     okeys[k] = orc.keygen_share(k)
         opks = [orc.aggregate_pk([okeys[k][1] for k in groups[gi]]) for gi in sample_groups]
-        c_end = min(C_, max(1, int(25 * 4096 * 3 / (N * L))))      # about 10-30 s of CPU work
+        c_end = min(C_, max(1, int(25 * 4096 * 3 / (N * L))))      # bounds the CPU work to tens of core-seconds
         t0 = time.perf_counter()
         threads = 1
         for gi in sample_groups:
