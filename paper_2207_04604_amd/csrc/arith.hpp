@@ -1,0 +1,433 @@
+// Modular arithmetic back-ends ("policies") for the transform engine on gfx950.
+//
+// On CDNA4 v_mad_u64_u32, v_mul_lo/hi_u32, v_lshl_add_u64 and v_fma_f64 all issue at full
+// rate, so the cost of a butterfly is its instruction count.  Three formulations, chosen
+// per context from the size of the largest modulus:
+//
+//   ArithF  (moduli < 2^44)  residues as signed doubles.  w*y mod q from an error-free
+//           product (mul + fma), one rounded quotient and one fma: 6 instructions, result
+//           in about (-q/2, q/2); butterflies add and subtract without any correction.
+//   ArithS  (moduli < 2^55)  64-bit integers, Shoup quotient ws = floor(w 2^63 / q).  The
+//           quotient estimate drops the low x low partial product (error <= 2), so the
+//           product lands in [0, 4q); values grow by at most 4q per forward stage and are
+//           never corrected inside a forward transform (65 q < 2^62).
+//   ArithB  (moduli < 2^61)  64-bit integers, exact 63-bit Shoup quotient, Harvey's lazy
+//           butterflies: forward values in [0, 4q), inverse values in [0, 2q).
+//
+// Table entries (twiddles, per-modulus constants) are {w, floor(w 2^63 / q)} for the integer
+// policies and {bits of the double w, unused} for ArithF.  Prepared keys cross the library
+// boundary as values plus 64-bit quotients floor(v 2^64 / q); the integer policies shift
+// those right by one, ArithF converts the value and ignores the quotient.
+#pragma once
+#include <stdint.h>
+
+#ifndef D2_DEV
+#define D2_DEV __device__ __forceinline__
+#endif
+
+#pragma clang fp contract(off)
+
+namespace d2 {
+
+struct Tw {          // 16-byte table entry: a fixed multiplicand and its companion word
+    uint64_t w;
+    uint64_t ws;
+};
+
+D2_DEV uint32_t lo32(uint64_t v) { return (uint32_t)v; }
+D2_DEV uint32_t hi32(uint64_t v) { return (uint32_t)(v >> 32); }
+D2_DEV uint64_t mul32(uint32_t a, uint32_t b) { return (uint64_t)a * b; }
+
+// The hot sequences are pinned with inline assembly on the device: the compiler's own
+// selection for the same C spends about 40 % more VALU slots (zero-extension moves, a compare
+// in front of every conditional subtraction, 32-bit multiplies split off the 64-bit
+// multiply-adds).  The plain C next to each block states what it computes and is what a
+// host build of this header runs.
+#if defined(__HIP_DEVICE_COMPILE__)
+#define D2_GCN_ASM 1
+#else
+#define D2_GCN_ASM 0
+#endif
+
+// x >= m ? x - m : x   (unsigned): subtract, then select on the borrow
+D2_DEV uint64_t csub(uint64_t x, uint64_t m)
+{
+#if D2_GCN_ASM
+    uint32_t dlo, dhi;
+    const uint32_t xlo = lo32(x), xhi = hi32(x), mlo = lo32(m), mhi = hi32(m);
+    asm("v_sub_co_u32 %0, vcc, %2, %4\n\t"
+        "v_subb_co_u32 %1, vcc, %3, %5, vcc\n\t"
+        "v_cndmask_b32 %0, %0, %2, vcc\n\t"
+        "v_cndmask_b32 %1, %1, %3, vcc"
+        : "=&v"(dlo), "=&v"(dhi)
+        : "v"(xlo), "v"(xhi), "v"(mlo), "v"(mhi)
+        : "vcc");
+    return ((uint64_t)dhi << 32) | dlo;
+#else
+    uint64_t d = x - m;
+    return x < m ? x : d;
+#endif
+}
+
+// floor(w * 2^64 / q) for w < q < 2^61 by binary long division (set-up paths only).
+D2_DEV uint64_t shoup_quotient(uint64_t w, uint64_t q)
+{
+    uint64_t rem = w, quo = 0;
+    for (int i = 0; i < 64; ++i) {
+        rem <<= 1;
+        quo <<= 1;
+        if (rem >= q) { rem -= q; quo |= 1; }
+    }
+    return quo;
+}
+
+// ---------------------------------------------------------------------------------------
+// Shared pieces of the two integer policies.
+// ---------------------------------------------------------------------------------------
+struct ModU {
+    uint64_t q;     // modulus
+    uint64_t nq;    // 2^64 - q
+    uint64_t one_s; // floor(2^63 / q): Shoup quotient of the multiplicand 1
+};
+
+struct TwU {        // multiplicand and its 63-bit Shoup quotient
+    uint64_t w, ws;
+};
+
+// w*y - qh*q mod 2^64, written as w*y + qh*(2^64 - q) so that every term is added:
+// a chain of four 64-bit multiply-adds for the cross terms (only its low word matters; it is
+// shifted up by 32), then two more for the low x low terms on top of it.
+D2_DEV uint64_t shoup_tail(uint64_t y, uint64_t w, uint64_t qh, uint64_t nq)
+{
+    const uint32_t y0 = lo32(y), y1 = hi32(y), w0 = lo32(w), w1 = hi32(w);
+    const uint32_t h0 = lo32(qh), h1 = hi32(qh), n0 = lo32(nq), n1 = hi32(nq);
+#if D2_GCN_ASM
+    uint64_t acc, cross;
+    asm("v_mad_u64_u32 %1, vcc, %4, %3, 0\n\t"
+        "v_mad_u64_u32 %1, vcc, %5, %2, %1\n\t"
+        "v_mad_u64_u32 %1, vcc, %6, %9, %1\n\t"
+        "v_mad_u64_u32 %1, vcc, %7, %8, %1\n\t"
+        "v_lshlrev_b64 %1, 32, %1\n\t"
+        "v_mad_u64_u32 %0, vcc, %4, %2, %1\n\t"
+        "v_mad_u64_u32 %0, vcc, %6, %8, %0"
+        : "=&v"(acc), "=&v"(cross)
+        : "v"(y0), "v"(y1), "v"(w0), "v"(w1), "v"(h0), "v"(h1), "v"(n0), "v"(n1)
+        : "vcc");
+    return acc;
+#else
+    uint64_t acc = mul32(w0, y0);
+    acc = mul32(h0, n0) + acc;
+    const uint32_t cross = w0 * y1 + w1 * y0 + h0 * n1 + h1 * n0;
+    return acc + ((uint64_t)cross << 32);
+#endif
+}
+
+// y*1 - qh*q mod 2^64 (reduction of y itself)
+D2_DEV uint64_t shoup_tail_one(uint64_t y, uint64_t qh, uint64_t nq)
+{
+    const uint32_t h0 = lo32(qh), h1 = hi32(qh), n0 = lo32(nq), n1 = hi32(nq);
+    uint64_t acc = mul32(h0, n0) + y;
+    const uint32_t cross = h0 * n1 + h1 * n0;
+    return acc + ((uint64_t)cross << 32);
+}
+
+// floor(ws*y / 2^63) up to an error of 2 (too small): drops the low x low partial product.
+// Needs ws < 2^63 and y < 2^63 (then the middle sum cannot overflow).
+D2_DEV uint64_t qhat_approx(uint64_t y, uint64_t ws)
+{
+    const uint32_t y0 = lo32(y), y1 = hi32(y), s0 = lo32(ws), s1 = hi32(ws);
+#if D2_GCN_ASM
+    uint64_t mid, top;
+    asm("v_mad_u64_u32 %0, vcc, %5, %2, 0\n\t"
+        "v_mad_u64_u32 %1, vcc, %5, %3, 0\n\t"
+        "v_mad_u64_u32 %0, vcc, %4, %3, %0\n\t"
+        "v_lshrrev_b64 %0, 31, %0\n\t"
+        "v_lshl_add_u64 %0, %1, 1, %0"
+        : "=&v"(mid), "=&v"(top)
+        : "v"(y0), "v"(y1), "v"(s0), "v"(s1)
+        : "vcc");
+    return mid;
+#else
+    uint64_t mid = mul32(s1, y0);
+    mid = mul32(s0, y1) + mid;
+    const uint64_t top = mul32(s1, y1);
+    return (top << 1) + (mid >> 31);
+#endif
+}
+
+// floor(ws*y / 2^63) exactly, for ws < 2^63 and y < 2^63.
+D2_DEV uint64_t qhat_exact(uint64_t y, uint64_t ws)
+{
+    const uint32_t y0 = lo32(y), y1 = hi32(y), s0 = lo32(ws), s1 = hi32(ws);
+#if D2_GCN_ASM
+    uint64_t mid, top;
+    asm("v_mad_u64_u32 %0, vcc, %4, %2, 0\n\t"
+        "v_mad_u64_u32 %1, vcc, %5, %3, 0\n\t"
+        "v_lshrrev_b64 %0, 32, %0\n\t"
+        "v_mad_u64_u32 %0, vcc, %5, %2, %0\n\t"
+        "v_mad_u64_u32 %0, vcc, %4, %3, %0\n\t"
+        "v_lshrrev_b64 %0, 31, %0\n\t"
+        "v_lshl_add_u64 %0, %1, 1, %0"
+        : "=&v"(mid), "=&v"(top)
+        : "v"(y0), "v"(y1), "v"(s0), "v"(s1)
+        : "vcc");
+    return mid;
+#else
+    uint64_t mid = mul32(s1, y0) + (uint64_t)__umulhi(s0, y0);
+    mid = mul32(s0, y1) + mid;
+    const uint64_t top = mul32(s1, y1);
+    return (top << 1) + (mid >> 31);
+#endif
+}
+
+// ---------------------------------------------------------------------------------------
+// ArithS: moduli < 2^55, lazy products in [0, 4q).
+// ---------------------------------------------------------------------------------------
+struct ArithS {
+    typedef uint64_t elem;
+    typedef ModU Mod;
+    typedef TwU Twid;
+    static constexpr int KIND = 1;
+
+    D2_DEV static Mod mod(uint64_t q) { return Mod{q, 0 - q, 0}; }
+    D2_DEV static Mod mod(uint64_t q, uint64_t one_s63) { return Mod{q, 0 - q, one_s63}; }
+    D2_DEV static Twid tw(const Tw &t) { return Twid{t.w, t.ws}; }
+    D2_DEV static Twid tw(uint64_t w, uint64_t ws64) { return Twid{w, ws64 >> 1}; }
+    D2_DEV static Twid load(const Tw *table, uint32_t i) { return tw(table[i]); }
+
+    // w*y mod q in [0, 4q), for y < 2^62.
+    D2_DEV static elem mul(elem y, const Twid &w, const Mod &m)
+    {
+        return shoup_tail(y, w.w, qhat_approx(y, w.ws), m.nq);
+    }
+    D2_DEV static elem from_small(int32_t v, const Mod &m)
+    {
+        return v >= 0 ? (uint64_t)v : m.q - (uint64_t)(uint32_t)(-v);
+    }
+    D2_DEV static elem from_canon(uint64_t v, const Mod &) { return v; }
+    D2_DEV static elem add(elem a, elem b) { return a + b; }
+
+    // forward: no correction; each stage adds at most 4q to the bound
+    D2_DEV static void ct(elem &x, elem &y, const Twid &w, const Mod &m)
+    {
+        const elem t = mul(y, w, m);
+        const elem u = x;
+        x = u + t;
+        y = u + 4 * m.q - t;
+    }
+    D2_DEV static void fwd_pass_begin(elem &, const Mod &) {}
+    // inverse: values in [0, 4q)
+    D2_DEV static void gs(elem &x, elem &y, const Twid &w, const Mod &m)
+    {
+        const elem four_q = 4 * m.q;
+        const elem s = x + y, d = x + four_q - y;
+        x = csub(s, four_q);
+        y = mul(d, w, m);
+    }
+    D2_DEV static void gs_last(elem &x, elem &y, const Twid &ninv, const Twid &wn, const Mod &m)
+    {
+        const elem s = x + y, d = x + 4 * m.q - y;
+        x = mul(s, ninv, m);
+        y = mul(d, wn, m);
+    }
+    D2_DEV static void inv_pass_begin(elem &, const Mod &) {}
+    D2_DEV static elem inv_input(uint64_t canon, const Mod &) { return canon; }
+
+    // any value < 2^62 -> [0, q)
+    D2_DEV static uint64_t canon_wide(elem x, const Mod &m)
+    {
+        const elem r = shoup_tail_one(x, qhat_exact(x, m.one_s), m.nq);   // [0, 2q)
+        return csub(r, m.q);
+    }
+    // [0, 4q) -> [0, q)
+    D2_DEV static uint64_t canon_lazy(elem x, const Mod &m) { return csub(csub(x, 2 * m.q), m.q); }
+    D2_DEV static uint64_t canon_fwd(elem x, const Mod &m) { return canon_wide(x, m); }
+    D2_DEV static uint64_t canon_inv(elem x, const Mod &m) { return canon_lazy(x, m); }
+    // forward output + one lazy product
+    D2_DEV static uint64_t canon_acc(elem x, const Mod &m) { return canon_wide(x, m); }
+};
+
+// ---------------------------------------------------------------------------------------
+// ArithB: moduli < 2^61, Harvey butterflies with an exact quotient.
+// ---------------------------------------------------------------------------------------
+struct ArithB {
+    typedef uint64_t elem;
+    typedef ModU Mod;
+    typedef TwU Twid;
+    static constexpr int KIND = 2;
+
+    D2_DEV static Mod mod(uint64_t q) { return Mod{q, 0 - q, 0}; }
+    D2_DEV static Mod mod(uint64_t q, uint64_t one_s63) { return Mod{q, 0 - q, one_s63}; }
+    D2_DEV static Twid tw(const Tw &t) { return Twid{t.w, t.ws}; }
+    D2_DEV static Twid tw(uint64_t w, uint64_t ws64) { return Twid{w, ws64 >> 1}; }
+    D2_DEV static Twid load(const Tw *table, uint32_t i) { return tw(table[i]); }
+
+    // w*y mod q in [0, 2q), for y < 2^63.
+    D2_DEV static elem mul(elem y, const Twid &w, const Mod &m)
+    {
+        return shoup_tail(y, w.w, qhat_exact(y, w.ws), m.nq);
+    }
+    D2_DEV static elem from_small(int32_t v, const Mod &m)
+    {
+        return v >= 0 ? (uint64_t)v : m.q - (uint64_t)(uint32_t)(-v);
+    }
+    D2_DEV static elem from_canon(uint64_t v, const Mod &) { return v; }
+    D2_DEV static elem add(elem a, elem b) { return a + b; }
+
+    // x, y in [0, 4q) -> [0, 4q)
+    D2_DEV static void ct(elem &x, elem &y, const Twid &w, const Mod &m)
+    {
+        const elem two_q = 2 * m.q;
+        const elem u = csub(x, two_q);
+        const elem t = mul(y, w, m);
+        x = u + t;
+        y = u + two_q - t;
+    }
+    D2_DEV static void fwd_pass_begin(elem &, const Mod &) {}
+    // x, y in [0, 2q) -> [0, 2q)
+    D2_DEV static void gs(elem &x, elem &y, const Twid &w, const Mod &m)
+    {
+        const elem two_q = 2 * m.q;
+        const elem s = x + y, d = x + two_q - y;
+        x = csub(s, two_q);
+        y = mul(d, w, m);
+    }
+    D2_DEV static void gs_last(elem &x, elem &y, const Twid &ninv, const Twid &wn, const Mod &m)
+    {
+        const elem s = x + y, d = x + 2 * m.q - y;
+        x = mul(s, ninv, m);
+        y = mul(d, wn, m);
+    }
+    D2_DEV static void inv_pass_begin(elem &, const Mod &) {}
+    D2_DEV static elem inv_input(uint64_t canon, const Mod &) { return canon; }
+
+    D2_DEV static uint64_t canon_lazy(elem x, const Mod &m) { return csub(csub(x, 2 * m.q), m.q); }
+    // any value < 2^63 -> [0, q)
+    D2_DEV static uint64_t canon_wide(elem x, const Mod &m)
+    {
+        const elem r = shoup_tail_one(x, qhat_exact(x, m.one_s), m.nq);
+        return csub(r, m.q);
+    }
+    D2_DEV static uint64_t canon_fwd(elem x, const Mod &m) { return canon_lazy(x, m); }
+    D2_DEV static uint64_t canon_inv(elem x, const Mod &m) { return csub(x, m.q); }
+    // forward output + one lazy product: [0, 6q)
+    D2_DEV static uint64_t canon_acc(elem x, const Mod &m) { return canon_lazy(csub(x, 4 * m.q), m); }
+};
+
+// ---------------------------------------------------------------------------------------
+// ArithF: moduli < 2^44, residues as doubles holding integers (signed representatives).
+// ---------------------------------------------------------------------------------------
+struct ArithF {
+    typedef double elem;
+    struct Mod {
+        double q, qinv;
+        uint64_t qi;
+    };
+    struct Twid {
+        double w;
+    };
+    static constexpr int KIND = 0;
+
+    D2_DEV static double u2d(uint64_t v)    // exact for v < 2^52
+    {
+        return __longlong_as_double((long long)(v | 0x4330000000000000ull)) - 4503599627370496.0;
+    }
+    D2_DEV static uint64_t d2u(double r)    // exact for integers 0 <= r < 2^52
+    {
+        return (uint64_t)__double_as_longlong(r + 4503599627370496.0) & 0x000fffffffffffffull;
+    }
+    D2_DEV static Mod mod(uint64_t q)
+    {
+        const double qd = u2d(q);
+        return Mod{qd, 1.0 / qd, q};
+    }
+    D2_DEV static Mod mod(uint64_t q, uint64_t) { return mod(q); }
+    D2_DEV static Twid tw(const Tw &t) { return Twid{__longlong_as_double((long long)t.w)}; }
+    D2_DEV static Twid tw(uint64_t w, uint64_t) { return Twid{u2d(w)}; }
+    D2_DEV static Twid load(const Tw *table, uint32_t i) { return Twid{((const double *)table)[2 * i]}; }
+
+    // x - round(x/q) q: about (-q/2, q/2)
+    D2_DEV static elem reduce(elem x, const Mod &m)
+    {
+        const double b = __builtin_rint(x * m.qinv);
+        return __builtin_fma(-b, m.q, x);
+    }
+    // w*y mod q as a signed representative of magnitude <= q/2 + 1, for |w y| < 2^96
+    D2_DEV static elem mul(elem y, const Twid &w, const Mod &m)
+    {
+        const double h = w.w * y;
+        const double l = __builtin_fma(w.w, y, -h);
+        const double b = __builtin_rint(h * m.qinv);
+        const double r = __builtin_fma(-b, m.q, h);
+        return r + l;
+    }
+    D2_DEV static elem from_small(int32_t v, const Mod &) { return (double)v; }
+    D2_DEV static elem from_canon(uint64_t v, const Mod &) { return u2d(v); }
+    D2_DEV static elem add(elem a, elem b) { return a + b; }
+
+    D2_DEV static void ct(elem &x, elem &y, const Twid &w, const Mod &m)
+    {
+        const elem t = mul(y, w, m);
+        const elem u = x;
+        x = u + t;
+        y = u - t;
+    }
+    D2_DEV static void fwd_pass_begin(elem &, const Mod &) {}
+    D2_DEV static void gs(elem &x, elem &y, const Twid &w, const Mod &m)
+    {
+        const elem s = x + y, d = x - y;
+        x = s;
+        y = mul(d, w, m);
+    }
+    D2_DEV static void gs_last(elem &x, elem &y, const Twid &ninv, const Twid &wn, const Mod &m)
+    {
+        const elem s = x + y, d = x - y;
+        x = mul(s, ninv, m);
+        y = mul(d, wn, m);
+    }
+    // the sum path of the inverse doubles every stage: bring it back once per pass
+    D2_DEV static void inv_pass_begin(elem &x, const Mod &m) { x = reduce(x, m); }
+    D2_DEV static elem inv_input(uint64_t canon, const Mod &) { return u2d(canon); }
+
+    D2_DEV static uint64_t canon_wide(elem x, const Mod &m)
+    {
+        double r = reduce(x, m);
+        r = r < 0.0 ? r + m.q : r;
+        r = r >= m.q ? r - m.q : r;
+        return d2u(r);
+    }
+    D2_DEV static uint64_t canon_lazy(elem x, const Mod &m) { return canon_wide(x, m); }
+    D2_DEV static uint64_t canon_fwd(elem x, const Mod &m) { return canon_wide(x, m); }
+    D2_DEV static uint64_t canon_inv(elem x, const Mod &m) { return canon_wide(x, m); }
+    D2_DEV static uint64_t canon_acc(elem x, const Mod &m) { return canon_wide(x, m); }
+};
+
+// canonical u64 helpers used outside the transforms
+D2_DEV uint64_t add_mod(uint64_t a, uint64_t b, uint64_t q) { return csub(a + b, q); }
+// w*y mod q, canonical, with the 64-bit Shoup quotient ws64 = floor(w 2^64 / q); any 64-bit y
+D2_DEV uint64_t mul_shoup64(uint64_t y, uint64_t w, uint64_t ws64, uint64_t q)
+{
+    const uint64_t r = w * y - __umul64hi(ws64, y) * q;
+    return csub(r, q);
+}
+
+// uint64 <-> element bit patterns for LDS and lazily stored intermediates
+template <class A>
+D2_DEV uint64_t to_bits(typename A::elem v);
+template <>
+D2_DEV uint64_t to_bits<ArithS>(uint64_t v) { return v; }
+template <>
+D2_DEV uint64_t to_bits<ArithB>(uint64_t v) { return v; }
+template <>
+D2_DEV uint64_t to_bits<ArithF>(double v) { return (uint64_t)__double_as_longlong(v); }
+
+template <class A>
+D2_DEV typename A::elem from_bits(uint64_t v);
+template <>
+D2_DEV uint64_t from_bits<ArithS>(uint64_t v) { return v; }
+template <>
+D2_DEV uint64_t from_bits<ArithB>(uint64_t v) { return v; }
+template <>
+D2_DEV double from_bits<ArithF>(uint64_t v) { return __longlong_as_double((long long)v); }
+
+}  // namespace d2

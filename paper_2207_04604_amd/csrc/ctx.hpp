@@ -13,6 +13,7 @@ struct d2mhe_ctx {
     uint64_t psi[d2::MAX_LIMBS + 1];
     uint64_t t;
     uint32_t max_group;
+    int arith;          // 0: ArithF, 1: ArithS, 2: ArithB
     d2::RoundConst rc;
     const d2::LimbTab *d_tabs;
     uint64_t *d_p1;     // prepared common random polynomial [2][L][N]
@@ -53,12 +54,26 @@ struct EngineOps {
                                    uint64_t n_values, hipStream_t);
 };
 
-const EngineOps *ops_10();
-const EngineOps *ops_11();
-const EngineOps *ops_12();
-const EngineOps *ops_13();
-const EngineOps *ops_14();
-const EngineOps *ops_15();
-const EngineOps *ops_16();
+const EngineOps *ops_f_10();
+const EngineOps *ops_f_11();
+const EngineOps *ops_f_12();
+const EngineOps *ops_f_13();
+const EngineOps *ops_f_14();
+const EngineOps *ops_f_15();
+const EngineOps *ops_f_16();
+const EngineOps *ops_s_10();
+const EngineOps *ops_s_11();
+const EngineOps *ops_s_12();
+const EngineOps *ops_s_13();
+const EngineOps *ops_s_14();
+const EngineOps *ops_s_15();
+const EngineOps *ops_s_16();
+const EngineOps *ops_b_10();
+const EngineOps *ops_b_11();
+const EngineOps *ops_b_12();
+const EngineOps *ops_b_13();
+const EngineOps *ops_b_14();
+const EngineOps *ops_b_15();
+const EngineOps *ops_b_16();
 
 }  // namespace d2

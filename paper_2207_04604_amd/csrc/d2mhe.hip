@@ -83,18 +83,39 @@ uint32_t h_bitrev(uint32_t v, int bits)
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- engine shape per ring degree ----------------------------------------------------------
-const EngineOps *engine_ops(uint32_t log2n)
+typedef const EngineOps *(*OpsGetter)();
+const OpsGetter OPS_TABLE[3][7] = {
+    {ops_f_10, ops_f_11, ops_f_12, ops_f_13, ops_f_14, ops_f_15, ops_f_16},
+    {ops_s_10, ops_s_11, ops_s_12, ops_s_13, ops_s_14, ops_s_15, ops_s_16},
+    {ops_b_10, ops_b_11, ops_b_12, ops_b_13, ops_b_14, ops_b_15, ops_b_16},
+};
+
+const EngineOps *engine_ops(const d2mhe_ctx *ctx) { return OPS_TABLE[ctx->arith][ctx->log2n - 10](); }
+
+// Arithmetic back-end from the largest modulus: doubles below 2^44, 63-bit Shoup with an
+// approximate quotient below 2^55, exact Harvey butterflies otherwise.
+int arith_for(const d2mhe_params *p)
 {
-    switch (log2n) {
-    case 10: return ops_10();
-    case 11: return ops_11();
-    case 12: return ops_12();
-    case 13: return ops_13();
-    case 14: return ops_14();
-    case 15: return ops_15();
-    case 16: return ops_16();
-    default: return nullptr;
+    uint64_t qmax = 0;
+    for (uint32_t i = 0; i < p->num_limbs; ++i) qmax = p->q[i] > qmax ? p->q[i] : qmax;
+    if (qmax < (1ull << 44)) return 0;
+    if (qmax < (1ull << 55)) return 1;
+    return 2;
+}
+
+// table entry in the format of the back-end
+Tw h_entry(int arith, uint64_t w, uint64_t m)
+{
+    Tw t;
+    if (arith == 0) {
+        const double d = (double)w;          // exact: w < 2^44
+        std::memcpy(&t.w, &d, sizeof(d));
+        t.ws = 0;
+    } else {
+        t.w = w;
+        t.ws = (uint64_t)(((unsigned __int128)w << 63) / m);
     }
+    return t;
 }
 
 struct Layout {
@@ -145,7 +166,7 @@ bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
 
 d2mhe_status launch_ntt(d2mhe_ctx *ctx, uint64_t *polys, uint32_t B, bool forward, hipStream_t st)
 {
-    return engine_ops(ctx->log2n)->ntt(ctx, polys, B, forward, st);
+    return engine_ops(ctx)->ntt(ctx, polys, B, forward, st);
 }
 
 }  // namespace
@@ -195,6 +216,8 @@ d2mhe_status d2mhe_create(const d2mhe_params *p, void *dev_workspace, size_t byt
     ctx->N = N;
     ctx->t = p->t;
     ctx->max_group = p->max_group;
+    ctx->arith = arith_for(p);
+    const int ar = ctx->arith;
     ctx->last_hip = 0;
     char *ws = (char *)dev_workspace;
     ctx->d_tabs = (const LimbTab *)(ws + lo.tabs_off);
@@ -216,25 +239,26 @@ d2mhe_status d2mhe_create(const d2mhe_params *p, void *dev_workspace, size_t byt
         Tw *fwd = tw.data() + (size_t)i * 2 * N, *inv = fwd + N;
         pw[0] = 1;
         for (size_t k = 1; k < N; ++k) pw[k] = h_mul(pw[k - 1], psi, m);
-        for (size_t k = 0; k < N; ++k) fwd[k] = h_tw(pw[h_bitrev((uint32_t)k, (int)log2n)], m);
+        for (size_t k = 0; k < N; ++k) fwd[k] = h_entry(ar, pw[h_bitrev((uint32_t)k, (int)log2n)], m);
         const uint64_t psi_inv = h_inv(psi, m);
         for (size_t k = 1; k < N; ++k) pw[k] = h_mul(pw[k - 1], psi_inv, m);
-        for (size_t k = 0; k < N; ++k) inv[k] = h_tw(pw[h_bitrev((uint32_t)k, (int)log2n)], m);
+        for (size_t k = 0; k < N; ++k) inv[k] = h_entry(ar, pw[h_bitrev((uint32_t)k, (int)log2n)], m);
         LimbTab &tb = tabs[i < L ? i : L];
         tb.q = m;
+        tb.one_s = (uint64_t)(((u128)1 << 63) / m);
         const uint64_t ninv = h_inv((uint64_t)N % m, m);
-        tb.ninv = h_tw(ninv, m);
-        tb.wn = h_tw(h_mul(inv[1].w, ninv, m), m);
+        tb.ninv = h_entry(ar, ninv, m);
+        tb.wn = h_entry(ar, h_mul(pw[h_bitrev(1u, (int)log2n)], ninv, m), m);   // inverse twiddle 1 times N^-1
         tb.fwd = (const Tw *)(ws + lo.tw_off) + (size_t)i * 2 * N;
         tb.inv = tb.fwd + N;
         if (i < L && has_t) {
             // floor(Q/t) = (Q - (Q mod t)) / t  and  Q = 0 (mod q_i)  =>  floor(Q/t) = -(Q mod t) t^-1 (mod q_i)
             const uint64_t lam = h_mul((m - q_mod_t % m) % m, h_inv(p->t % m, m), m);
-            tb.lambda = h_tw(lam, m);
+            tb.lambda = h_entry(ar, lam, m);
             uint64_t others = 1;
             for (uint32_t j = 0; j < L; ++j)
                 if (j != i) others = h_mul(others, p->q[j] % m, m);
-            tb.gamma = h_tw(h_inv(others, m), m);
+            tb.gamma = h_tw(h_inv(others, m), m);      // always the integer pair
             const u128 num = (u128)p->t << 64;
             tb.theta_hi = (uint64_t)(num / m);
             tb.theta_lo = (uint64_t)(((num % m) << 64) / m);
@@ -298,7 +322,7 @@ uint64_t d2mhe_root(const d2mhe_ctx *ctx, uint32_t limb)
 d2mhe_status d2mhe_ntt_index_map(const d2mhe_ctx *ctx, uint32_t *perm)
 {
     if (!ctx || !perm) return D2MHE_ERR_NULL;
-    const EngineOps *ops = engine_ops(ctx->log2n);
+    const EngineOps *ops = engine_ops(ctx);
     const int elog = ops->elog, logb = ops->logb;
     const uint32_t T = 1u << (logb - elog), NB = 1u << logb;
     for (uint32_t pos = 0; pos < ctx->N; ++pos) {
@@ -353,7 +377,7 @@ d2mhe_status d2mhe_keygen_share(d2mhe_ctx *ctx, uint32_t party, uint64_t *sk_sha
     if (!sk_share || !pk0_share) return D2MHE_ERR_NULL;
     if (misaligned(sk_share) || misaligned(pk0_share)) return D2MHE_ERR_ALIGN;
     if (party > 0xffffu) return D2MHE_ERR_RANGE;
-    return engine_ops(ctx->log2n)->keygen(ctx, party, sk_share, pk0_share, (hipStream_t)stream);
+    return engine_ops(ctx)->keygen(ctx, party, sk_share, pk0_share, (hipStream_t)stream);
 }
 
 d2mhe_status d2mhe_aggregate_pk(d2mhe_ctx *ctx, const uint64_t *const *pk0_shares, uint32_t K, uint64_t *pk,
@@ -386,7 +410,7 @@ d2mhe_status d2mhe_encode(d2mhe_ctx *ctx, const float *grad, uint64_t n_values, 
     if (misaligned(pt) || misaligned(grad)) return D2MHE_ERR_ALIGN;
     if (n_values > (uint64_t)C * ctx->N) return D2MHE_ERR_RANGE;
     if (C == 0) return D2MHE_OK;
-    return engine_ops(ctx->log2n)->encode(ctx, grad, n_values, pt, C, (hipStream_t)stream);
+    return engine_ops(ctx)->encode(ctx, grad, n_values, pt, C, (hipStream_t)stream);
 }
 
 d2mhe_status d2mhe_decode(d2mhe_ctx *ctx, const uint64_t *pt, uint32_t C, uint64_t n_values, float *out,
@@ -397,7 +421,7 @@ d2mhe_status d2mhe_decode(d2mhe_ctx *ctx, const uint64_t *pt, uint32_t C, uint64
     if (misaligned(pt) || misaligned(out)) return D2MHE_ERR_ALIGN;
     if (n_values > (uint64_t)C * ctx->N) return D2MHE_ERR_RANGE;
     if (C == 0) return D2MHE_OK;
-    return engine_ops(ctx->log2n)->decode(ctx, pt, C, n_values, out, (hipStream_t)stream);
+    return engine_ops(ctx)->decode(ctx, pt, C, n_values, out, (hipStream_t)stream);
 }
 
 d2mhe_status d2mhe_encrypt(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_t *pt, uint32_t C, uint32_t party,
@@ -414,7 +438,7 @@ d2mhe_status d2mhe_encrypt(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_t *p
     jobs.out[0] = ct;
     jobs.party[0] = party;
     jobs.group[0] = group;
-    return engine_ops(ctx->log2n)->encrypt(ctx, false, jobs, 1, ct_base, 0, C, (hipStream_t)stream);
+    return engine_ops(ctx)->encrypt(ctx, false, jobs, 1, ct_base, 0, C, (hipStream_t)stream);
 }
 
 d2mhe_status d2mhe_add(d2mhe_ctx *ctx, uint64_t *ct_acc, const uint64_t *ct_in, uint32_t C, void *stream)
@@ -447,7 +471,7 @@ d2mhe_status d2mhe_partial_decrypt(d2mhe_ctx *ctx, const uint64_t *sk_share, con
     jobs.out[0] = share;
     jobs.party[0] = party;
     jobs.group[0] = group;
-    return engine_ops(ctx->log2n)->share(ctx, jobs, 1, ct_base, C, (hipStream_t)stream);
+    return engine_ops(ctx)->share(ctx, jobs, 1, ct_base, C, (hipStream_t)stream);
 }
 
 d2mhe_status d2mhe_combine(d2mhe_ctx *ctx, const uint64_t *ct, const uint64_t *const *shares, uint32_t K, uint32_t C,
@@ -464,7 +488,7 @@ d2mhe_status d2mhe_combine(d2mhe_ctx *ctx, const uint64_t *ct, const uint64_t *c
         sh.p[k] = shares[k];
     }
     if (C == 0) return D2MHE_OK;
-    return engine_ops(ctx->log2n)->combine(ctx, ct, sh, K, C, pt, (hipStream_t)stream);
+    return engine_ops(ctx)->combine(ctx, ct, sh, K, C, pt, (hipStream_t)stream);
 }
 
 namespace {
@@ -522,7 +546,7 @@ d2mhe_status d2mhe_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, void *scratc
     uint64_t *agg = cts + (size_t)J * ct_words;
     uint64_t *shares = agg + (size_t)G * ct_words;
     hipStream_t st = (hipStream_t)stream;
-    const EngineOps *ops = engine_ops(ctx->log2n);
+    const EngineOps *ops = engine_ops(ctx);
     hipEvent_t *ev = (hipEvent_t *)phase_events;
     if (ev) D2_HIP(ctx, hipEventRecord(ev[0], st));
 

@@ -20,13 +20,13 @@ struct Launch {
             constexpr int LOGN = ENG::LOGN, LOGH = LOGN - ENG::LOGB;
             dim3 hgrid((1u << (LOGN - LOGH)) / 256, polys_n), tgrid(1u << LOGH, polys_n);
             if (forward) {
-                hipLaunchKernelGGL((k_head_forward<LOGN, LOGH>), hgrid, dim3(256), 0, st, polys, ctx->d_tabs, L);
+                hipLaunchKernelGGL((k_head_forward<typename ENG::A, LOGN, LOGH>), hgrid, dim3(256), 0, st, polys, ctx->d_tabs, L);
                 D2_LAUNCHED(ctx);
                 hipLaunchKernelGGL(k_tail_forward<ENG>, tgrid, dim3(ENG::T), 0, st, polys, ctx->d_tabs, L);
             } else {
                 hipLaunchKernelGGL(k_tail_inverse<ENG>, tgrid, dim3(ENG::T), 0, st, polys, ctx->d_tabs, L);
                 D2_LAUNCHED(ctx);
-                hipLaunchKernelGGL((k_head_inverse<LOGN, LOGH>), hgrid, dim3(256), 0, st, polys, ctx->d_tabs, L);
+                hipLaunchKernelGGL((k_head_inverse<typename ENG::A, LOGN, LOGH>), hgrid, dim3(256), 0, st, polys, ctx->d_tabs, L);
             }
             D2_LAUNCHED(ctx);
         }

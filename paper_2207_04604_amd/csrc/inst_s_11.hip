@@ -1,0 +1,10 @@
+// Kernel instantiations: ring degree 2^11, arithmetic ArithS.
+#include "engine_inst.hpp"
+
+namespace d2 {
+const EngineOps *ops_s_11()
+{
+    static const EngineOps ops = Launch<Engine<ArithS, 11, 4>>::full();
+    return &ops;
+}
+}

@@ -1,7 +1,6 @@
 // HIP kernels of the exchange round.  One workgroup owns one polynomial (or one ciphertext
 // and walks over its RNS limbs); transforms run in registers + LDS (ntt_engine.hpp).
 #pragma once
-#include "mod64.hpp"
 #include "ntt_engine.hpp"
 #include "philox.hpp"
 
@@ -11,12 +10,16 @@ constexpr int MAX_LIMBS = 16;
 constexpr int MAX_GROUP = 64;
 
 // Per-modulus constants; entry L of the table array describes the plaintext modulus t.
+// Tw entries are in the context's arithmetic format ({w, floor(w 2^63/q)} for the integer
+// policies, {bits of the double w, -} for the floating-point policy), except `gamma`, which
+// is always {w, floor(w 2^64/q)} (the scale-and-round step runs on canonical integers).
 struct LimbTab {
     uint64_t q;
+    uint64_t one_s;     // floor(2^63 / q)
     Tw ninv;            // N^-1 mod q
     Tw wn;              // (inverse twiddle 1) * N^-1 mod q
     Tw lambda;          // floor(Q/t) mod q
-    Tw gamma;           // (Q/q)^-1 mod q
+    Tw gamma;           // (Q/q)^-1 mod q, integer pair
     uint64_t theta_hi;  // floor(t * 2^128 / q), high and low words
     uint64_t theta_lo;
     const Tw *fwd;      // forward twiddles, N entries
@@ -68,144 +71,146 @@ D2_DEV uint32_t bitrev(uint32_t v, int bits) { return __brev(v) >> (32 - bits); 
 template <class ENG>
 __global__ void __launch_bounds__(ENG::T) k_ntt_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L)
 {
+    typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
-    const uint32_t limb = blockIdx.x % L;
-    const LimbTab &tb = tabs[limb];
-    const uint64_t q = tb.q;
+    const LimbTab &tb = tabs[blockIdx.x % L];
+    const typename A::Mod md = A::mod(tb.q, tb.one_s);
     uint64_t *p = polys + (size_t)blockIdx.x * ENG::NB;
-    uint64_t x[ENG::E];
+    typename A::elem x[ENG::E];
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) x[k] = p[ENG::coef_pos(k, tid)];
-    ENG::forward(x, lds, tid, 0, tb.fwd, q);
+    for (int k = 0; k < ENG::E; ++k) x[k] = A::from_canon(p[ENG::coef_pos(k, tid)], md);
+    ENG::forward(x, lds, tid, 0, tb.fwd, md);
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) p[ENG::eval_pos(k, tid)] = reduce4(x[k], q);
+    for (int k = 0; k < ENG::E; ++k) p[ENG::eval_pos(k, tid)] = A::canon_fwd(x[k], md);
 }
 
 template <class ENG>
 __global__ void __launch_bounds__(ENG::T) k_ntt_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L)
 {
+    typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
-    const uint32_t limb = blockIdx.x % L;
-    const LimbTab &tb = tabs[limb];
-    const uint64_t q = tb.q;
+    const LimbTab &tb = tabs[blockIdx.x % L];
+    const typename A::Mod md = A::mod(tb.q, tb.one_s);
     uint64_t *p = polys + (size_t)blockIdx.x * ENG::NB;
-    uint64_t x[ENG::E];
+    typename A::elem x[ENG::E];
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) x[k] = p[ENG::eval_pos(k, tid)];
-    ENG::template inverse<true>(x, lds, tid, 0, tb.inv, q, tb.ninv, tb.wn);
+    for (int k = 0; k < ENG::E; ++k) x[k] = A::inv_input(p[ENG::eval_pos(k, tid)], md);
+    ENG::template inverse<true>(x, lds, tid, 0, tb.inv, md, A::tw(tb.ninv), A::tw(tb.wn));
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) p[ENG::coef_pos(k, tid)] = csub(x[k], q);
+    for (int k = 0; k < ENG::E; ++k) p[ENG::coef_pos(k, tid)] = A::canon_inv(x[k], md);
 }
 
 // -------------------------------------------------------------------------------------
 // Transforms longer than one workgroup can hold: the top LOGH = LOGN - LOGB stages couple
 // the 2^LOGH blocks of NB coefficients ("head", register-only, strided global access); the
 // remaining LOGB stages are independent per block ("tail", the engine with a block id).
+// Between the two kernels the data stays in the policy's lazy representation.
 // -------------------------------------------------------------------------------------
-template <int LOGN, int LOGH>
+template <class A, int LOGN, int LOGH>
 __global__ void __launch_bounds__(256) k_head_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L)
 {
     constexpr int H = 1 << LOGH;
     constexpr int STRIDE = 1 << (LOGN - LOGH);
     const uint32_t poly = blockIdx.y;
     const LimbTab &tb = tabs[poly % L];
-    const uint64_t q = tb.q;
+    const typename A::Mod md = A::mod(tb.q, tb.one_s);
     const Tw *tw = tb.fwd;
     uint64_t *p = polys + ((size_t)poly << LOGN) + (size_t)blockIdx.x * 256 + threadIdx.x;
-    uint64_t x[H];
+    typename A::elem x[H];
 #pragma unroll
-    for (int k = 0; k < H; ++k) x[k] = p[(size_t)k * STRIDE];
+    for (int k = 0; k < H; ++k) x[k] = A::from_canon(p[(size_t)k * STRIDE], md);
 #pragma unroll
     for (int kb = LOGH - 1; kb >= 0; --kb) {
         const int s = LOGH - 1 - kb;
 #pragma unroll
         for (int g = 0; g < (H >> (kb + 1)); ++g) {
-            const Tw w = tw[(1 << s) + g];
+            const typename A::Twid w = A::load(tw, (1u << s) + g);
 #pragma unroll
             for (int j = 0; j < (1 << kb); ++j) {
                 const int k0 = (g << (kb + 1)) | j;
-                ct_butterfly(x[k0], x[k0 | (1 << kb)], w.w, w.ws, q);
+                A::ct(x[k0], x[k0 | (1 << kb)], w, md);
             }
         }
     }
 #pragma unroll
-    for (int k = 0; k < H; ++k) p[(size_t)k * STRIDE] = x[k];   // stays lazy, < 4q
+    for (int k = 0; k < H; ++k) p[(size_t)k * STRIDE] = to_bits<A>(x[k]);   // stays lazy
 }
 
-template <int LOGN, int LOGH>
+template <class A, int LOGN, int LOGH>
 __global__ void __launch_bounds__(256) k_head_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L)
 {
     constexpr int H = 1 << LOGH;
     constexpr int STRIDE = 1 << (LOGN - LOGH);
     const uint32_t poly = blockIdx.y;
     const LimbTab &tb = tabs[poly % L];
-    const uint64_t q = tb.q, two_q = 2 * q;
+    const typename A::Mod md = A::mod(tb.q, tb.one_s);
     const Tw *tw = tb.inv;
     uint64_t *p = polys + ((size_t)poly << LOGN) + (size_t)blockIdx.x * 256 + threadIdx.x;
-    uint64_t x[H];
+    typename A::elem x[H];
 #pragma unroll
-    for (int k = 0; k < H; ++k) x[k] = p[(size_t)k * STRIDE];   // in [0, 2q)
+    for (int k = 0; k < H; ++k) {
+        x[k] = from_bits<A>(p[(size_t)k * STRIDE]);               // lazy, from the tail kernel
+        A::inv_pass_begin(x[k], md);
+    }
 #pragma unroll
     for (int kb = 0; kb < LOGH; ++kb) {
         const int s = LOGH - 1 - kb;
         if (kb == LOGH - 1) {                                    // last stage: fold N^-1
 #pragma unroll
-            for (int j = 0; j < (1 << kb); ++j) {
-                uint64_t a = x[j], c = x[j | (1 << kb)];
-                x[j] = mul_shoup_lazy(a + c, tb.ninv.w, tb.ninv.ws, q);
-                x[j | (1 << kb)] = mul_shoup_lazy(a - c + two_q, tb.wn.w, tb.wn.ws, q);
-            }
+            for (int j = 0; j < (1 << kb); ++j) A::gs_last(x[j], x[j | (1 << kb)], A::tw(tb.ninv), A::tw(tb.wn), md);
         } else {
 #pragma unroll
             for (int g = 0; g < (H >> (kb + 1)); ++g) {
-                const Tw w = tw[(1 << s) + g];
+                const typename A::Twid w = A::load(tw, (1u << s) + g);
 #pragma unroll
                 for (int j = 0; j < (1 << kb); ++j) {
                     const int k0 = (g << (kb + 1)) | j;
-                    gs_butterfly(x[k0], x[k0 | (1 << kb)], w.w, w.ws, q);
+                    A::gs(x[k0], x[k0 | (1 << kb)], w, md);
                 }
             }
         }
     }
 #pragma unroll
-    for (int k = 0; k < H; ++k) p[(size_t)k * STRIDE] = csub(x[k], q);
+    for (int k = 0; k < H; ++k) p[(size_t)k * STRIDE] = A::canon_inv(x[k], md);
 }
 
 // tail: grid.x = blocks per polynomial, grid.y = polynomial index (b * L + limb)
 template <class ENG>
 __global__ void __launch_bounds__(ENG::T) k_tail_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L)
 {
+    typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
     const uint32_t poly = blockIdx.y, blk = blockIdx.x;
     const LimbTab &tb = tabs[poly % L];
-    const uint64_t q = tb.q;
+    const typename A::Mod md = A::mod(tb.q, tb.one_s);
     uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
-    uint64_t x[ENG::E];
+    typename A::elem x[ENG::E];
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) x[k] = p[ENG::coef_pos(k, tid)];
-    ENG::forward(x, lds, tid, blk, tb.fwd, q);
+    for (int k = 0; k < ENG::E; ++k) x[k] = from_bits<A>(p[ENG::coef_pos(k, tid)]);
+    ENG::forward(x, lds, tid, blk, tb.fwd, md);
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) p[ENG::eval_pos(k, tid)] = reduce4(x[k], q);
+    for (int k = 0; k < ENG::E; ++k) p[ENG::eval_pos(k, tid)] = A::canon_fwd(x[k], md);
 }
 
 template <class ENG>
 __global__ void __launch_bounds__(ENG::T) k_tail_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L)
 {
+    typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
     const uint32_t poly = blockIdx.y, blk = blockIdx.x;
     const LimbTab &tb = tabs[poly % L];
-    const uint64_t q = tb.q;
+    const typename A::Mod md = A::mod(tb.q, tb.one_s);
     uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
-    uint64_t x[ENG::E];
+    typename A::elem x[ENG::E];
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) x[k] = p[ENG::eval_pos(k, tid)];
-    ENG::template inverse<false>(x, lds, tid, blk, tb.inv, q, tb.ninv, tb.wn);
+    for (int k = 0; k < ENG::E; ++k) x[k] = A::inv_input(p[ENG::eval_pos(k, tid)], md);
+    ENG::template inverse<false>(x, lds, tid, blk, tb.inv, md, A::tw(tb.ninv), A::tw(tb.wn));
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) p[ENG::coef_pos(k, tid)] = x[k];   // [0, 2q), head finishes
+    for (int k = 0; k < ENG::E; ++k) p[ENG::coef_pos(k, tid)] = to_bits<A>(x[k]);   // lazy, head finishes
 }
 
 // -------------------------------------------------------------------------------------
@@ -250,10 +255,12 @@ D2_DEV int32_t sbyte(uint32_t w, int i) { return (int32_t)(int8_t)(w >> (8 * i))
 // ciphertext index c in registers in pass-0 (natural) ownership, values in [0, t).
 // -------------------------------------------------------------------------------------
 template <class ENG>
-D2_DEV void encode_to_regs(uint64_t (&x)[ENG::E], uint64_t *lds, int tid, const float *grad, uint64_t first,
+D2_DEV void encode_to_regs(uint32_t (&m)[ENG::E], uint64_t *lds, int tid, const float *grad, uint64_t first,
                            uint64_t n_values, const LimbTab &tt, const RoundConst &rc)
 {
+    typedef typename ENG::A A;
     const uint64_t t = tt.q;
+    const typename A::Mod md = A::mod(t, tt.one_s);
     __syncthreads();
     for (int j = tid; j < ENG::NB; j += ENG::T) {
         uint64_t gi = first + (uint64_t)j;
@@ -267,25 +274,31 @@ D2_DEV void encode_to_regs(uint64_t (&x)[ENG::E], uint64_t *lds, int tid, const 
     }
     __syncthreads();
     // slot j is the evaluation xhat[j], which the engine keeps at block index bitrev(j)
+    typename A::elem x[ENG::E];
 #pragma unroll
     for (int k = 0; k < ENG::E; ++k)
-        x[k] = lds[ENG::phys((int)bitrev((uint32_t)(tid * ENG::E + k), ENG::LOGB))];
-    ENG::template inverse<true>(x, lds, tid, 0, tt.inv, t, tt.ninv, tt.wn);
+        x[k] = A::inv_input(lds[ENG::phys((int)bitrev((uint32_t)(tid * ENG::E + k), ENG::LOGB))], md);
+    ENG::template inverse<true>(x, lds, tid, 0, tt.inv, md, A::tw(tt.ninv), A::tw(tt.wn));
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) x[k] = csub(x[k], t);
+    for (int k = 0; k < ENG::E; ++k) m[k] = (uint32_t)A::canon_inv(x[k], md);
 }
 
 // registers hold a plaintext polynomial (natural ownership, [0,t)) -> floats
 template <class ENG>
-D2_DEV void decode_from_regs(uint64_t (&x)[ENG::E], uint64_t *lds, int tid, float *out, uint64_t first,
+D2_DEV void decode_from_regs(uint32_t (&m)[ENG::E], uint64_t *lds, int tid, float *out, uint64_t first,
                              uint64_t n_values, const LimbTab &tt, const RoundConst &rc)
 {
+    typedef typename ENG::A A;
     const uint64_t t = tt.q;
-    ENG::forward(x, lds, tid, 0, tt.fwd, t);
+    const typename A::Mod md = A::mod(t, tt.one_s);
+    typename A::elem x[ENG::E];
+#pragma unroll
+    for (int k = 0; k < ENG::E; ++k) x[k] = A::from_canon((uint64_t)m[k], md);
+    ENG::forward(x, lds, tid, 0, tt.fwd, md);
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < ENG::E; ++k)
-        lds[ENG::phys((int)bitrev((uint32_t)(tid * ENG::E + k), ENG::LOGB))] = reduce4(x[k], t);
+        lds[ENG::phys((int)bitrev((uint32_t)(tid * ENG::E + k), ENG::LOGB))] = A::canon_fwd(x[k], md);
     __syncthreads();
     for (int j = tid; j < ENG::NB; j += ENG::T) {
         uint64_t gi = first + (uint64_t)j;
@@ -304,10 +317,10 @@ __global__ void __launch_bounds__(ENG::T) k_encode(const float *grad, uint64_t n
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
-    uint64_t x[ENG::E];
-    encode_to_regs<ENG>(x, lds, tid, grad, (uint64_t)c * ENG::NB, n_values, tabs[rc.L], rc);
+    uint32_t m[ENG::E];
+    encode_to_regs<ENG>(m, lds, tid, grad, (uint64_t)c * ENG::NB, n_values, tabs[rc.L], rc);
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) pt[(size_t)c * ENG::NB + ENG::coef_pos(k, tid)] = x[k];
+    for (int k = 0; k < ENG::E; ++k) pt[(size_t)c * ENG::NB + ENG::coef_pos(k, tid)] = m[k];
 }
 
 template <class ENG>
@@ -317,10 +330,10 @@ __global__ void __launch_bounds__(ENG::T) k_decode(const uint64_t *pt, uint64_t 
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
-    uint64_t x[ENG::E];
+    uint32_t m[ENG::E];
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) x[k] = pt[(size_t)c * ENG::NB + ENG::coef_pos(k, tid)];
-    decode_from_regs<ENG>(x, lds, tid, out, (uint64_t)c * ENG::NB, n_values, tabs[rc.L], rc);
+    for (int k = 0; k < ENG::E; ++k) m[k] = (uint32_t)pt[(size_t)c * ENG::NB + ENG::coef_pos(k, tid)];
+    decode_from_regs<ENG>(m, lds, tid, out, (uint64_t)c * ENG::NB, n_values, tabs[rc.L], rc);
 }
 
 // -------------------------------------------------------------------------------------
@@ -332,14 +345,16 @@ template <class ENG>
 __global__ void __launch_bounds__(ENG::T) k_keygen(uint32_t party, uint64_t *sk, uint64_t *pk0, const uint64_t *p1,
                                                    const LimbTab *tabs, RoundConst rc)
 {
+    typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     uint32_t *lds32 = (uint32_t *)lds;
     const int tid = threadIdx.x;
     const uint32_t limb = blockIdx.x, L = rc.L;
     const LimbTab &tb = tabs[limb];
     const uint64_t q = tb.q;
+    const typename A::Mod md = A::mod(q, tb.one_s);
     const size_t LN = (size_t)L * ENG::NB, off = (size_t)limb * ENG::NB;
-    uint64_t s[ENG::E], e[ENG::E];
+    typename A::elem s[ENG::E], e[ENG::E];
     // secret share: ternary, counter (block, 0, party, SK)
     for (int j = tid; j < ENG::NB / 4; j += ENG::T) {
         int32_t v[4];
@@ -349,22 +364,22 @@ __global__ void __launch_bounds__(ENG::T) k_keygen(uint32_t party, uint64_t *sk,
     }
     __syncthreads();
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) s[k] = lift_small((int32_t)lds32[ENG::coef_pos(k, tid)], q);
+    for (int k = 0; k < ENG::E; ++k) s[k] = A::from_small((int32_t)lds32[ENG::coef_pos(k, tid)], md);
     __syncthreads();
     stage_cbd<ENG>(lds32, tid, DOM_PK_E, party, 0, 0, rc);
     __syncthreads();
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) e[k] = lift_small((int32_t)lds32[ENG::coef_pos(k, tid)], q);
-    ENG::forward(s, lds, tid, 0, tb.fwd, q);
-    ENG::forward(e, lds, tid, 0, tb.fwd, q);
+    for (int k = 0; k < ENG::E; ++k) e[k] = A::from_small((int32_t)lds32[ENG::coef_pos(k, tid)], md);
+    ENG::forward(s, lds, tid, 0, tb.fwd, md);
+    ENG::forward(e, lds, tid, 0, tb.fwd, md);
 #pragma unroll
     for (int k = 0; k < ENG::E; ++k) {
         const int pos = ENG::eval_pos(k, tid);
-        uint64_t sv = reduce4(s[k], q);
+        const uint64_t sv = A::canon_fwd(s[k], md);
         sk[off + pos] = sv;
         sk[LN + off + pos] = shoup_quotient(sv, q);
-        uint64_t prod = mul_shoup(sv, p1[off + pos], p1[LN + off + pos], q);   // p1 * s
-        uint64_t sum = add_mod(prod, reduce4(e[k], q), q);
+        const typename A::elem prod = A::mul(A::from_canon(sv, md), A::tw(p1[off + pos], p1[LN + off + pos]), md);
+        const uint64_t sum = A::canon_acc(A::add(prod, e[k]), md);      // p1 s + e
         pk0[off + pos] = sum == 0 ? 0 : q - sum;
     }
 }
@@ -379,6 +394,8 @@ template <class ENG, bool FROM_FLOAT>
 __global__ void __launch_bounds__(ENG::T) k_encrypt(EncJobs jobs, uint32_t ct_base, uint64_t n_values,
                                                     const LimbTab *tabs, RoundConst rc)
 {
+    typedef typename ENG::A A;
+    typedef typename A::elem elem;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     uint32_t *lds32 = (uint32_t *)lds;
     constexpr int E = ENG::E;
@@ -390,18 +407,12 @@ __global__ void __launch_bounds__(ENG::T) k_encrypt(EncJobs jobs, uint32_t ct_ba
     uint64_t *out = jobs.out[job] + (size_t)c * 2 * LN;
 
     uint32_t m[E];
-    {
-        uint64_t x[E];
-        if (FROM_FLOAT) {
-            encode_to_regs<ENG>(x, lds, tid, (const float *)jobs.src[job], (uint64_t)c * ENG::NB, n_values,
-                                tabs[L], rc);
-        } else {
-            const uint64_t *pt = (const uint64_t *)jobs.src[job] + (size_t)c * ENG::NB;
+    if (FROM_FLOAT) {
+        encode_to_regs<ENG>(m, lds, tid, (const float *)jobs.src[job], (uint64_t)c * ENG::NB, n_values, tabs[L], rc);
+    } else {
+        const uint64_t *pt = (const uint64_t *)jobs.src[job] + (size_t)c * ENG::NB;
 #pragma unroll
-            for (int k = 0; k < E; ++k) x[k] = pt[ENG::coef_pos(k, tid)];
-        }
-#pragma unroll
-        for (int k = 0; k < E; ++k) m[k] = (uint32_t)x[k];
+        for (int k = 0; k < E; ++k) m[k] = (uint32_t)pt[ENG::coef_pos(k, tid)];
     }
     uint32_t smp[E];
     __syncthreads();
@@ -412,32 +423,31 @@ __global__ void __launch_bounds__(ENG::T) k_encrypt(EncJobs jobs, uint32_t ct_ba
 
     for (uint32_t limb = 0; limb < L; ++limb) {
         const LimbTab &tb = tabs[limb];
-        const uint64_t q = tb.q;
+        const typename A::Mod md = A::mod(tb.q, tb.one_s);
+        const typename A::Twid lam = A::tw(tb.lambda);
         const size_t off = (size_t)limb * ENG::NB;
         const uint64_t *p0 = pk + off, *p0s = pk + LN + off;
         const uint64_t *p1 = pk + 2 * LN + off, *p1s = pk + 3 * LN + off;
-        uint64_t u[E], x[E];
+        elem u[E], x[E];
 #pragma unroll
-        for (int k = 0; k < E; ++k) u[k] = lift_small(sbyte(smp[k], 0), q);
-        ENG::forward(u, lds, tid, 0, tb.fwd, q);
+        for (int k = 0; k < E; ++k) u[k] = A::from_small(sbyte(smp[k], 0), md);
+        ENG::forward(u, lds, tid, 0, tb.fwd, md);
 #pragma unroll
         for (int k = 0; k < E; ++k)
-            x[k] = add_mod(mul_shoup((uint64_t)m[k], tb.lambda.w, tb.lambda.ws, q), lift_small(sbyte(smp[k], 1), q), q);
-        ENG::forward(x, lds, tid, 0, tb.fwd, q);
+            x[k] = A::add(A::mul(A::from_canon((uint64_t)m[k], md), lam, md), A::from_small(sbyte(smp[k], 1), md));
+        ENG::forward(x, lds, tid, 0, tb.fwd, md);
 #pragma unroll
         for (int k = 0; k < E; ++k) {
             const int pos = ENG::eval_pos(k, tid);
-            uint64_t v = mul_shoup_lazy(u[k], p0[pos], p0s[pos], q) + x[k];   // < 6q
-            out[off + pos] = reduce4(csub(v, 4 * q), q);
+            out[off + pos] = A::canon_acc(A::add(A::mul(u[k], A::tw(p0[pos], p0s[pos]), md), x[k]), md);
         }
 #pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = lift_small(sbyte(smp[k], 2), q);
-        ENG::forward(x, lds, tid, 0, tb.fwd, q);
+        for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(smp[k], 2), md);
+        ENG::forward(x, lds, tid, 0, tb.fwd, md);
 #pragma unroll
         for (int k = 0; k < E; ++k) {
             const int pos = ENG::eval_pos(k, tid);
-            uint64_t v = mul_shoup_lazy(u[k], p1[pos], p1s[pos], q) + x[k];
-            out[LN + off + pos] = reduce4(csub(v, 4 * q), q);
+            out[LN + off + pos] = A::canon_acc(A::add(A::mul(u[k], A::tw(p1[pos], p1s[pos]), md), x[k]), md);
         }
     }
 }
@@ -448,6 +458,7 @@ __global__ void __launch_bounds__(ENG::T) k_encrypt(EncJobs jobs, uint32_t ct_ba
 template <class ENG>
 __global__ void __launch_bounds__(ENG::T) k_share(ShareJobs jobs, uint32_t ct_base, const LimbTab *tabs, RoundConst rc)
 {
+    typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     uint32_t *lds32 = (uint32_t *)lds;
     constexpr int E = ENG::E;
@@ -457,25 +468,25 @@ __global__ void __launch_bounds__(ENG::T) k_share(ShareJobs jobs, uint32_t ct_ba
     const uint64_t *sk = jobs.sk[job];
     const uint64_t *c1 = jobs.ct[job] + ((size_t)c * 2 + 1) * LN;
     uint64_t *out = jobs.out[job] + (size_t)c * LN;
-    const uint32_t group = jobs.group[job];
     int32_t e[E];
-    stage_cbd<ENG>(lds32, tid, DOM_DEC_E, jobs.party[job], group, ct_base + c, rc);
+    stage_cbd<ENG>(lds32, tid, DOM_DEC_E, jobs.party[job], jobs.group[job], ct_base + c, rc);
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < E; ++k) e[k] = (int32_t)lds32[ENG::coef_pos(k, tid)];
     for (uint32_t limb = 0; limb < L; ++limb) {
         const LimbTab &tb = tabs[limb];
-        const uint64_t q = tb.q;
+        const typename A::Mod md = A::mod(tb.q, tb.one_s);
         const size_t off = (size_t)limb * ENG::NB;
-        uint64_t x[E];
+        typename A::elem x[E];
 #pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = lift_small(e[k], q);
-        ENG::forward(x, lds, tid, 0, tb.fwd, q);
+        for (int k = 0; k < E; ++k) x[k] = A::from_small(e[k], md);
+        ENG::forward(x, lds, tid, 0, tb.fwd, md);
 #pragma unroll
         for (int k = 0; k < E; ++k) {
             const int pos = ENG::eval_pos(k, tid);
-            uint64_t v = mul_shoup_lazy(c1[off + pos], sk[off + pos], sk[LN + off + pos], q) + x[k];
-            out[off + pos] = reduce4(csub(v, 4 * q), q);
+            const typename A::elem prod =
+                A::mul(A::from_canon(c1[off + pos], md), A::tw(sk[off + pos], sk[LN + off + pos]), md);
+            out[off + pos] = A::canon_acc(A::add(prod, x[k]), md);
         }
     }
 }
@@ -485,13 +496,13 @@ __global__ void __launch_bounds__(ENG::T) k_share(ShareJobs jobs, uint32_t ct_ba
 // by summing t * y_i' / q_i over the limbs with y_i' = y_i (Q/q_i)^-1 mod q_i: integer
 // parts exactly, fractional parts in 64-bit fixed point (each term is truncated by less
 // than 2^-63, so the rounding is exact unless t y / Q lies within L * 2^-63 of a half-integer).
-// grid = C.  DECODE: continue to floats instead of storing the plaintext polynomial.
-// -------------------------------------------------------------------------------------
 // SH(j) returns the share buffer [C][L][N] of member j.
+// -------------------------------------------------------------------------------------
 template <class ENG, bool DECODE, class SH>
 D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_t K, uint64_t *pt, float *out,
                          uint64_t n_values, const LimbTab *tabs, const RoundConst &rc)
 {
+    typedef typename ENG::A A;
     constexpr int E = ENG::E;
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x, L = rc.L;
@@ -503,22 +514,26 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
     for (uint32_t limb = 0; limb < L; ++limb) {
         const LimbTab &tb = tabs[limb];
         const uint64_t q = tb.q;
+        const typename A::Mod md = A::mod(q, tb.one_s);
         const size_t off = (size_t)limb * ENG::NB;
-        uint64_t x[E];
+        uint64_t y[E];
 #pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = c0[off + ENG::eval_pos(k, tid)];
+        for (int k = 0; k < E; ++k) y[k] = c0[off + ENG::eval_pos(k, tid)];
         for (uint32_t j = 0; j < K; ++j) {
             const uint64_t *h = share_of(j) + (size_t)c * LN + off;
 #pragma unroll
-            for (int k = 0; k < E; ++k) x[k] = add_mod(x[k], h[ENG::eval_pos(k, tid)], q);
+            for (int k = 0; k < E; ++k) y[k] = add_mod(y[k], h[ENG::eval_pos(k, tid)], q);
         }
-        ENG::template inverse<true>(x, lds, tid, 0, tb.inv, q, tb.ninv, tb.wn);
+        typename A::elem x[E];
+#pragma unroll
+        for (int k = 0; k < E; ++k) x[k] = A::inv_input(y[k], md);
+        ENG::template inverse<true>(x, lds, tid, 0, tb.inv, md, A::tw(tb.ninv), A::tw(tb.wn));
 #pragma unroll
         for (int k = 0; k < E; ++k) {
-            uint64_t y = mul_shoup(csub(x[k], q), tb.gamma.w, tb.gamma.ws, q);   // y_i'
-            // y * theta / 2^128 = integer part, next 64 bits = fraction (theta = floor(t 2^128 / q))
-            uint64_t hi_lo = y * tb.theta_hi, hi_hi = __umul64hi(y, tb.theta_hi);
-            uint64_t lo_hi = __umul64hi(y, tb.theta_lo);
+            const uint64_t yi = mul_shoup64(A::canon_inv(x[k], md), tb.gamma.w, tb.gamma.ws, q);   // y_i'
+            // yi * theta / 2^128 = integer part, next 64 bits = fraction (theta = floor(t 2^128 / q))
+            uint64_t hi_lo = yi * tb.theta_hi, hi_hi = __umul64hi(yi, tb.theta_hi);
+            uint64_t lo_hi = __umul64hi(yi, tb.theta_lo);
             uint64_t frac = hi_lo + lo_hi;
             uint64_t ip = hi_hi + (frac < hi_lo ? 1 : 0);
             uint64_t nf = acc_frac[k] + frac;
@@ -527,9 +542,9 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
         }
     }
     const uint64_t t = rc.t;
-    uint64_t m[E];
+    uint32_t m[E];
 #pragma unroll
-    for (int k = 0; k < E; ++k) m[k] = (acc_int[k] + (acc_frac[k] >> 63)) % t;   // + 1/2, floor
+    for (int k = 0; k < E; ++k) m[k] = (uint32_t)((acc_int[k] + (acc_frac[k] >> 63)) % t);   // + 1/2, floor
     if (DECODE) {
         decode_from_regs<ENG>(m, lds, tid, out, (uint64_t)c * ENG::NB, n_values, tabs[L], rc);
     } else {

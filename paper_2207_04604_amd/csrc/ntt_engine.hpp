@@ -20,13 +20,19 @@
 // Pass 0 has wb = LOGB - ELOG (idx = k * T + tid: coalesced natural order); the last pass
 // has wb = 0 (idx = tid * E + k), and evaluation-form data is stored at position
 // k * T + tid, so global accesses are coalesced on both sides.
+//
+// The arithmetic (element type, butterflies, lazy ranges) comes from a policy A (arith.hpp).
 #pragma once
-#include "mod64.hpp"
+#include "arith.hpp"
 
 namespace d2 {
 
-template <int LOGN_, int ELOG_, int LOGB_ = LOGN_>
+template <class A_, int LOGN_, int ELOG_, int LOGB_ = LOGN_>
 struct Engine {
+    typedef A_ A;
+    typedef typename A::elem elem;
+    typedef typename A::Mod Mod;
+    typedef typename A::Twid Twid;
     static constexpr int LOGN = LOGN_, ELOG = ELOG_, LOGB = LOGB_;
     static constexpr int NB = 1 << LOGB;
     static constexpr int E = 1 << ELOG;
@@ -57,8 +63,7 @@ struct Engine {
     D2_DEV static int coef_pos(int k, int tid) { return k * T + tid; }
 
     template <int P>
-    D2_DEV static void fwd_pass(uint64_t (&x)[E], int tid, uint32_t blk, const Tw *__restrict__ tw,
-                                uint64_t q)
+    D2_DEV static void fwd_pass(elem (&x)[E], int tid, uint32_t blk, const Tw *__restrict__ tw, const Mod &md)
     {
         constexpr int wb = wbase(P), lo = sbit(P), r = stages(P);
         const uint32_t hi = (uint32_t)(tid >> wb);
@@ -70,11 +75,11 @@ struct Engine {
             const uint32_t base = (1u << s) + (blk << (LOGB - b - 1)) + (hi << (ELOG - kb - 1));
 #pragma unroll
             for (int g = 0; g < (E >> (kb + 1)); ++g) {    // distinct twiddles of this stage
-                const Tw w = tw[base + g];
+                const Twid w = A::load(tw, base + g);
 #pragma unroll
                 for (int j = 0; j < (1 << kb); ++j) {
                     const int k0 = (g << (kb + 1)) | j;
-                    ct_butterfly(x[k0], x[k0 | (1 << kb)], w.w, w.ws, q);
+                    A::ct(x[k0], x[k0 | (1 << kb)], w, md);
                 }
             }
         }
@@ -83,32 +88,31 @@ struct Engine {
     // FOLD: this pass contains the last stage of the whole inverse transform (bit LOGN-1)
     // and multiplies by N^-1 there: ninv = N^-1, wn = (inverse twiddle 1) * N^-1.
     template <int P, bool FOLD>
-    D2_DEV static void inv_pass(uint64_t (&x)[E], int tid, uint32_t blk, const Tw *__restrict__ tw,
-                                uint64_t q, Tw ninv, Tw wn)
+    D2_DEV static void inv_pass(elem (&x)[E], int tid, uint32_t blk, const Tw *__restrict__ tw, const Mod &md,
+                                const Twid &ninv, const Twid &wn)
     {
         constexpr int wb = wbase(P), lo = sbit(P), r = stages(P);
         const uint32_t hi = (uint32_t)(tid >> wb);
+        if (P != NPASS - 1) {
+#pragma unroll
+            for (int k = 0; k < E; ++k) A::inv_pass_begin(x[k], md);
+        }
 #pragma unroll
         for (int b = lo; b < lo + r; ++b) {
             const int kb = b - wb;
             const int s = LOGN - 1 - b;
             const uint32_t base = (1u << s) + (blk << (LOGB - b - 1)) + (hi << (ELOG - kb - 1));
             if (FOLD && b == LOGN - 1) {
-                const uint64_t two_q = 2 * q;
 #pragma unroll
-                for (int j = 0; j < (1 << kb); ++j) {
-                    uint64_t a = x[j], c = x[j | (1 << kb)];
-                    x[j] = mul_shoup_lazy(a + c, ninv.w, ninv.ws, q);
-                    x[j | (1 << kb)] = mul_shoup_lazy(a - c + two_q, wn.w, wn.ws, q);
-                }
+                for (int j = 0; j < (1 << kb); ++j) A::gs_last(x[j], x[j | (1 << kb)], ninv, wn, md);
             } else {
 #pragma unroll
                 for (int g = 0; g < (E >> (kb + 1)); ++g) {
-                    const Tw w = tw[base + g];
+                    const Twid w = A::load(tw, base + g);
 #pragma unroll
                     for (int j = 0; j < (1 << kb); ++j) {
                         const int k0 = (g << (kb + 1)) | j;
-                        gs_butterfly(x[k0], x[k0 | (1 << kb)], w.w, w.ws, q);
+                        A::gs(x[k0], x[k0 | (1 << kb)], w, md);
                     }
                 }
             }
@@ -117,52 +121,51 @@ struct Engine {
 
     // Hand the coefficients from the owners of pass PF to the owners of pass PT.
     template <int PF, int PT>
-    D2_DEV static void exchange(uint64_t (&x)[E], uint64_t *lds, int tid)
+    D2_DEV static void exchange(elem (&x)[E], uint64_t *lds, int tid)
     {
         __syncthreads();                       // earlier readers of lds are done
 #pragma unroll
-        for (int k = 0; k < E; ++k) lds[phys(index_of<PF>(k, tid))] = x[k];
+        for (int k = 0; k < E; ++k) lds[phys(index_of<PF>(k, tid))] = to_bits<A>(x[k]);
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = lds[phys(index_of<PT>(k, tid))];
+        for (int k = 0; k < E; ++k) x[k] = from_bits<A>(lds[phys(index_of<PT>(k, tid))]);
     }
 
     template <int P>
-    D2_DEV static void fwd_from(uint64_t (&x)[E], uint64_t *lds, int tid, uint32_t blk,
-                                const Tw *__restrict__ tw, uint64_t q)
+    D2_DEV static void fwd_from(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
+                                const Mod &md)
     {
-        fwd_pass<P>(x, tid, blk, tw, q);
+        fwd_pass<P>(x, tid, blk, tw, md);
         if constexpr (P + 1 < NPASS) {
             exchange<P, P + 1>(x, lds, tid);
-            fwd_from<P + 1>(x, lds, tid, blk, tw, q);
+            fwd_from<P + 1>(x, lds, tid, blk, tw, md);
         }
     }
 
     template <int P, bool FOLD>
-    D2_DEV static void inv_from(uint64_t (&x)[E], uint64_t *lds, int tid, uint32_t blk,
-                                const Tw *__restrict__ tw, uint64_t q, Tw ninv, Tw wn)
+    D2_DEV static void inv_from(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
+                                const Mod &md, const Twid &ninv, const Twid &wn)
     {
-        inv_pass<P, FOLD>(x, tid, blk, tw, q, ninv, wn);
+        inv_pass<P, FOLD>(x, tid, blk, tw, md, ninv, wn);
         if constexpr (P > 0) {
             exchange<P, P - 1>(x, lds, tid);
-            inv_from<P - 1, FOLD>(x, lds, tid, blk, tw, q, ninv, wn);
+            inv_from<P - 1, FOLD>(x, lds, tid, blk, tw, md, ninv, wn);
         }
     }
 
-    // x: pass-0 ownership, values in [0, 4q)  ->  last-pass ownership, values in [0, 4q).
-    D2_DEV static void forward(uint64_t (&x)[E], uint64_t *lds, int tid, uint32_t blk,
-                               const Tw *__restrict__ tw, uint64_t q)
+    // x: pass-0 ownership (policy's forward input range) -> last-pass ownership, lazy.
+    D2_DEV static void forward(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
+                               const Mod &md)
     {
-        fwd_from<0>(x, lds, tid, blk, tw, q);
+        fwd_from<0>(x, lds, tid, blk, tw, md);
     }
 
-    // x: last-pass ownership, values in [0, 2q)  ->  pass-0 ownership, values in [0, 2q),
-    // scaled by N^-1 when FOLD.
+    // x: last-pass ownership (canonical input) -> pass-0 ownership, lazy; scaled by N^-1 when FOLD.
     template <bool FOLD>
-    D2_DEV static void inverse(uint64_t (&x)[E], uint64_t *lds, int tid, uint32_t blk,
-                               const Tw *__restrict__ tw, uint64_t q, Tw ninv, Tw wn)
+    D2_DEV static void inverse(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
+                               const Mod &md, const Twid &ninv, const Twid &wn)
     {
-        inv_from<NPASS - 1, FOLD>(x, lds, tid, blk, tw, q, ninv, wn);
+        inv_from<NPASS - 1, FOLD>(x, lds, tid, blk, tw, md, ninv, wn);
     }
 };
 
