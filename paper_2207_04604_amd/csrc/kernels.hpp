@@ -65,11 +65,60 @@ struct GroupJobs {                     // one job = one group: K buffers laid ou
 
 D2_DEV uint32_t bitrev(uint32_t v, int bits) { return __brev(v) >> (32 - bits); }
 
+// Global accesses through raw buffer instructions: a wave-uniform base (descriptor in SGPRs),
+// one 32-bit per-lane byte offset shared by every array and register slot, and a uniform
+// offset per slot.  Plain 64-bit addressing would hold a VGPR pair per array and slot.
+// The ranges are < 4 GB from the base.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+D2_DEV uint64_t ld64(const uint64_t *base, uint32_t lane_off, uint32_t slot_off)
+{
+#if D2_GCN_ASM
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, 0xffffffff, 0x00020000);
+    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, lane_off, slot_off, 0);
+    return ((uint64_t)v.y << 32) | v.x;
+#else
+    return *(const uint64_t *)((const char *)base + lane_off + slot_off);
+#endif
+}
+D2_DEV void st64(uint64_t *base, uint32_t lane_off, uint32_t slot_off, uint64_t val)
+{
+#if D2_GCN_ASM
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, 0xffffffff, 0x00020000);
+    u32x2 v;
+    v.x = (uint32_t)val;
+    v.y = (uint32_t)(val >> 32);
+    __builtin_amdgcn_raw_buffer_store_b64(v, r, lane_off, slot_off, 0);
+#else
+    *(uint64_t *)((char *)base + lane_off + slot_off) = val;
+#endif
+}
+
+// Returns v unchanged but opaque to the optimiser.  Used at the top of per-limb loops so that
+// per-thread addresses and sample conversions are recomputed per iteration (a few
+// instructions) instead of being hoisted and kept in ~100 registers across the whole loop.
+D2_DEV int opaque(int v)
+{
+#if D2_GCN_ASM
+    asm volatile("" : "+v"(v));
+#endif
+    return v;
+}
+D2_DEV uint32_t opaque(uint32_t v) { return (uint32_t)opaque((int)v); }
+// The same for a (wave-uniform) table pointer: two transforms in one loop body would otherwise
+// share their twiddle loads and keep all of them (~90 registers) alive from one to the next.
+D2_DEV const Tw *opaque(const Tw *p)
+{
+#if D2_GCN_ASM
+    asm volatile("" : "+v"(p));
+#endif
+    return p;
+}
+
 // -------------------------------------------------------------------------------------
 // Plain batched transforms: polys [B][L][N] in place, one workgroup per (b, limb).
 // -------------------------------------------------------------------------------------
 template <class ENG>
-__global__ void __launch_bounds__(ENG::T) k_ntt_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L)
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_ntt_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L)
 {
     typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
@@ -86,7 +135,7 @@ __global__ void __launch_bounds__(ENG::T) k_ntt_forward(uint64_t *polys, const L
 }
 
 template <class ENG>
-__global__ void __launch_bounds__(ENG::T) k_ntt_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L)
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_ntt_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L)
 {
     typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
@@ -178,7 +227,7 @@ __global__ void __launch_bounds__(256) k_head_inverse(uint64_t *polys, const Lim
 
 // tail: grid.x = blocks per polynomial, grid.y = polynomial index (b * L + limb)
 template <class ENG>
-__global__ void __launch_bounds__(ENG::T) k_tail_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L)
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L)
 {
     typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
@@ -196,7 +245,7 @@ __global__ void __launch_bounds__(ENG::T) k_tail_forward(uint64_t *polys, const 
 }
 
 template <class ENG>
-__global__ void __launch_bounds__(ENG::T) k_tail_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L)
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L)
 {
     typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
@@ -311,7 +360,7 @@ D2_DEV void decode_from_regs(uint32_t (&m)[ENG::E], uint64_t *lds, int tid, floa
 }
 
 template <class ENG>
-__global__ void __launch_bounds__(ENG::T) k_encode(const float *grad, uint64_t n_values, uint64_t *pt,
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encode(const float *grad, uint64_t n_values, uint64_t *pt,
                                                    const LimbTab *tabs, RoundConst rc)
 {
     __shared__ uint64_t lds[ENG::LDS_WORDS];
@@ -324,7 +373,7 @@ __global__ void __launch_bounds__(ENG::T) k_encode(const float *grad, uint64_t n
 }
 
 template <class ENG>
-__global__ void __launch_bounds__(ENG::T) k_decode(const uint64_t *pt, uint64_t n_values, float *out,
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_decode(const uint64_t *pt, uint64_t n_values, float *out,
                                                    const LimbTab *tabs, RoundConst rc)
 {
     __shared__ uint64_t lds[ENG::LDS_WORDS];
@@ -342,7 +391,7 @@ __global__ void __launch_bounds__(ENG::T) k_decode(const uint64_t *pt, uint64_t 
 // p1 is the prepared common random polynomial.
 // -------------------------------------------------------------------------------------
 template <class ENG>
-__global__ void __launch_bounds__(ENG::T) k_keygen(uint32_t party, uint64_t *sk, uint64_t *pk0, const uint64_t *p1,
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_keygen(uint32_t party, uint64_t *sk, uint64_t *pk0, const uint64_t *p1,
                                                    const LimbTab *tabs, RoundConst rc)
 {
     typedef typename ENG::A A;
@@ -391,7 +440,7 @@ __global__ void __launch_bounds__(ENG::T) k_keygen(uint32_t party, uint64_t *sk,
 // otherwise it is read from pt [C][N].
 // -------------------------------------------------------------------------------------
 template <class ENG, bool FROM_FLOAT>
-__global__ void __launch_bounds__(ENG::T) k_encrypt(EncJobs jobs, uint32_t ct_base, uint64_t n_values,
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, uint32_t ct_base, uint64_t n_values,
                                                     const LimbTab *tabs, RoundConst rc)
 {
     typedef typename ENG::A A;
@@ -428,26 +477,41 @@ __global__ void __launch_bounds__(ENG::T) k_encrypt(EncJobs jobs, uint32_t ct_ba
         const size_t off = (size_t)limb * ENG::NB;
         const uint64_t *p0 = pk + off, *p0s = pk + LN + off;
         const uint64_t *p1 = pk + 2 * LN + off, *p1s = pk + 3 * LN + off;
-        elem u[E], x[E];
+        const int tl = opaque(tid);
+        // NTT(mu) is parked (lazy, as raw bits) in the c1 slot of the output, which every thread
+        // re-reads at its own positions and overwrites last; keeping it in registers across the
+        // next two transforms would cost 2 E registers and halve the occupancy.
+        uint64_t *stash = out + LN + off;
+        {
+            elem u[E];
 #pragma unroll
-        for (int k = 0; k < E; ++k) u[k] = A::from_small(sbyte(smp[k], 0), md);
-        ENG::forward(u, lds, tid, 0, tb.fwd, md);
+            for (int k = 0; k < E; ++k) u[k] = A::from_small(sbyte(opaque(smp[k]), 0), md);
+            ENG::forward(u, lds, tl, 0, opaque(tb.fwd), md);
+#pragma unroll
+            for (int k = 0; k < E; ++k) st64(stash, 8u * (uint32_t)tl, 8u * ENG::T * k, to_bits<A>(u[k]));
+        }
+        elem x[E];
 #pragma unroll
         for (int k = 0; k < E; ++k)
-            x[k] = A::add(A::mul(A::from_canon((uint64_t)m[k], md), lam, md), A::from_small(sbyte(smp[k], 1), md));
-        ENG::forward(x, lds, tid, 0, tb.fwd, md);
+            x[k] = A::add(A::mul(A::from_canon((uint64_t)opaque(m[k]), md), lam, md),
+                          A::from_small(sbyte(opaque(smp[k]), 1), md));
+        ENG::forward(x, lds, opaque(tl), 0, opaque(tb.fwd), md);
 #pragma unroll
         for (int k = 0; k < E; ++k) {
-            const int pos = ENG::eval_pos(k, tid);
-            out[off + pos] = A::canon_acc(A::add(A::mul(u[k], A::tw(p0[pos], p0s[pos]), md), x[k]), md);
+            const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
+            const elem u = from_bits<A>(ld64(stash, lo, so));
+            st64(out + off, lo, so,
+                 A::canon_acc(A::add(A::mul(u, A::tw(ld64(p0, lo, so), ld64(p0s, lo, so)), md), x[k]), md));
         }
 #pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(smp[k], 2), md);
-        ENG::forward(x, lds, tid, 0, tb.fwd, md);
+        for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(opaque(smp[k]), 2), md);
+        ENG::forward(x, lds, opaque(tl), 0, opaque(tb.fwd), md);
 #pragma unroll
         for (int k = 0; k < E; ++k) {
-            const int pos = ENG::eval_pos(k, tid);
-            out[LN + off + pos] = A::canon_acc(A::add(A::mul(u[k], A::tw(p1[pos], p1s[pos]), md), x[k]), md);
+            const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
+            const elem u = from_bits<A>(ld64(stash, lo, so));
+            st64(stash, lo, so,
+                 A::canon_acc(A::add(A::mul(u, A::tw(ld64(p1, lo, so), ld64(p1s, lo, so)), md), x[k]), md));
         }
     }
 }
@@ -456,7 +520,7 @@ __global__ void __launch_bounds__(ENG::T) k_encrypt(EncJobs jobs, uint32_t ct_ba
 // Decryption share h = s c1 + e in evaluation form.  grid = (C, jobs).
 // -------------------------------------------------------------------------------------
 template <class ENG>
-__global__ void __launch_bounds__(ENG::T) k_share(ShareJobs jobs, uint32_t ct_base, const LimbTab *tabs, RoundConst rc)
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_share(ShareJobs jobs, uint32_t ct_base, const LimbTab *tabs, RoundConst rc)
 {
     typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
@@ -468,25 +532,26 @@ __global__ void __launch_bounds__(ENG::T) k_share(ShareJobs jobs, uint32_t ct_ba
     const uint64_t *sk = jobs.sk[job];
     const uint64_t *c1 = jobs.ct[job] + ((size_t)c * 2 + 1) * LN;
     uint64_t *out = jobs.out[job] + (size_t)c * LN;
-    int32_t e[E];
+    int e[E];
     stage_cbd<ENG>(lds32, tid, DOM_DEC_E, jobs.party[job], jobs.group[job], ct_base + c, rc);
     __syncthreads();
 #pragma unroll
-    for (int k = 0; k < E; ++k) e[k] = (int32_t)lds32[ENG::coef_pos(k, tid)];
+    for (int k = 0; k < E; ++k) e[k] = (int)lds32[ENG::coef_pos(k, tid)];
     for (uint32_t limb = 0; limb < L; ++limb) {
         const LimbTab &tb = tabs[limb];
         const typename A::Mod md = A::mod(tb.q, tb.one_s);
         const size_t off = (size_t)limb * ENG::NB;
+        const int tl = opaque(tid);
         typename A::elem x[E];
 #pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = A::from_small(e[k], md);
-        ENG::forward(x, lds, tid, 0, tb.fwd, md);
+        for (int k = 0; k < E; ++k) x[k] = A::from_small(opaque(e[k]), md);
+        ENG::forward(x, lds, tl, 0, tb.fwd, md);
 #pragma unroll
         for (int k = 0; k < E; ++k) {
-            const int pos = ENG::eval_pos(k, tid);
-            const typename A::elem prod =
-                A::mul(A::from_canon(c1[off + pos], md), A::tw(sk[off + pos], sk[LN + off + pos]), md);
-            out[off + pos] = A::canon_acc(A::add(prod, x[k]), md);
+            const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
+            const typename A::elem prod = A::mul(A::from_canon(ld64(c1 + off, lo, so), md),
+                                                 A::tw(ld64(sk + off, lo, so), ld64(sk + LN + off, lo, so)), md);
+            st64(out + off, lo, so, A::canon_acc(A::add(prod, x[k]), md));
         }
     }
 }
@@ -516,18 +581,19 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
         const uint64_t q = tb.q;
         const typename A::Mod md = A::mod(q, tb.one_s);
         const size_t off = (size_t)limb * ENG::NB;
+        const int tl = opaque(tid);
         uint64_t y[E];
 #pragma unroll
-        for (int k = 0; k < E; ++k) y[k] = c0[off + ENG::eval_pos(k, tid)];
+        for (int k = 0; k < E; ++k) y[k] = ld64(c0 + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
         for (uint32_t j = 0; j < K; ++j) {
             const uint64_t *h = share_of(j) + (size_t)c * LN + off;
 #pragma unroll
-            for (int k = 0; k < E; ++k) y[k] = add_mod(y[k], h[ENG::eval_pos(k, tid)], q);
+            for (int k = 0; k < E; ++k) y[k] = add_mod(y[k], ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k), q);
         }
         typename A::elem x[E];
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = A::inv_input(y[k], md);
-        ENG::template inverse<true>(x, lds, tid, 0, tb.inv, md, A::tw(tb.ninv), A::tw(tb.wn));
+        ENG::template inverse<true>(x, lds, tl, 0, tb.inv, md, A::tw(tb.ninv), A::tw(tb.wn));
 #pragma unroll
         for (int k = 0; k < E; ++k) {
             const uint64_t yi = mul_shoup64(A::canon_inv(x[k], md), tb.gamma.w, tb.gamma.ws, q);   // y_i'
@@ -555,7 +621,7 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
 
 // one aggregate, K share buffers anywhere in memory, plaintext polynomials out; grid = C
 template <class ENG>
-__global__ void __launch_bounds__(ENG::T) k_combine(const uint64_t *ct, PtrList shares, uint32_t K, uint64_t *pt,
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_combine(const uint64_t *ct, PtrList shares, uint32_t K, uint64_t *pt,
                                                     const LimbTab *tabs, RoundConst rc)
 {
     __shared__ uint64_t lds[ENG::LDS_WORDS];
@@ -565,7 +631,7 @@ __global__ void __launch_bounds__(ENG::T) k_combine(const uint64_t *ct, PtrList 
 
 // whole round: grid = (C, groups); the group's shares lie `stride` words apart; decoded floats out
 template <class ENG>
-__global__ void __launch_bounds__(ENG::T) k_combine_decode(GroupJobs jobs, size_t stride, uint64_t n_values,
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_combine_decode(GroupJobs jobs, size_t stride, uint64_t n_values,
                                                            const LimbTab *tabs, RoundConst rc)
 {
     __shared__ uint64_t lds[ENG::LDS_WORDS];

@@ -39,6 +39,7 @@ struct Engine {
     static constexpr int T = NB / E;
     static constexpr int NPASS = (LOGB + ELOG - 1) / ELOG;
     static constexpr int LDS_WORDS = NB + (NB >> ELOG);   // one pad word per E coefficients
+    static constexpr int WAVES = 4;   // waves per SIMD the kernels are compiled for (<= 128 VGPRs)
 
     static_assert(LOGB >= ELOG && LOGB <= LOGN, "bad engine shape");
 
@@ -119,16 +120,30 @@ struct Engine {
         }
     }
 
+    // LDS word of register slot k of thread tid in pass P = slot_base<P>(tid) + slot_off<P>(k):
+    // the thread bits and the slot bits of an index are disjoint, so the padded address splits
+    // into a per-thread base and a compile-time offset (an instruction immediate).
+    template <int P>
+    D2_DEV static int slot_base(int tid) { return phys(index_of<P>(0, tid)); }
+    template <int P>
+    static constexpr int slot_off(int k)
+    {
+        constexpr int wb = wbase(P);
+        return (k << wb) + ((k << wb) >> ELOG);
+    }
+
     // Hand the coefficients from the owners of pass PF to the owners of pass PT.
     template <int PF, int PT>
     D2_DEV static void exchange(elem (&x)[E], uint64_t *lds, int tid)
     {
+        uint64_t *wr = lds + slot_base<PF>(tid);
+        const uint64_t *rd = lds + slot_base<PT>(tid);
         __syncthreads();                       // earlier readers of lds are done
 #pragma unroll
-        for (int k = 0; k < E; ++k) lds[phys(index_of<PF>(k, tid))] = to_bits<A>(x[k]);
+        for (int k = 0; k < E; ++k) wr[slot_off<PF>(k)] = to_bits<A>(x[k]);
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = from_bits<A>(lds[phys(index_of<PT>(k, tid))]);
+        for (int k = 0; k < E; ++k) x[k] = from_bits<A>(rd[slot_off<PT>(k)]);
     }
 
     template <int P>
