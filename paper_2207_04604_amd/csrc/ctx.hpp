@@ -17,6 +17,7 @@ struct d2mhe_ctx {
     d2::RoundConst rc;
     const d2::LimbTab *d_tabs;
     uint64_t *d_p1;     // prepared common random polynomial [2][L][N]
+    uint32_t ntt_chunk_polys;   // polynomials per head/tail launch pair for N > 2^14 (0: all at once)
     int last_hip;
 };
 

@@ -219,6 +219,10 @@ d2mhe_status d2mhe_create(const d2mhe_params *p, void *dev_workspace, size_t byt
     ctx->arith = arith_for(p);
     const int ar = ctx->arith;
     ctx->last_hip = 0;
+    // Long transforms run as launch pairs over at most 65535 polynomials (grid.y limit).  Smaller
+    // chunks (to keep a chunk in the memory-side cache between the two kernels) were measured
+    // and bring nothing on MI355X: the strided kernel already runs at copy speed.
+    ctx->ntt_chunk_polys = 65535;
     char *ws = (char *)dev_workspace;
     ctx->d_tabs = (const LimbTab *)(ws + lo.tabs_off);
     ctx->d_p1 = has_t ? (uint64_t *)(ws + lo.p1_off) : nullptr;
@@ -338,7 +342,7 @@ d2mhe_status d2mhe_ntt_forward(d2mhe_ctx *ctx, uint64_t *polys, uint32_t B, void
     if (!ctx || !polys) return D2MHE_ERR_NULL;
     if (misaligned(polys)) return D2MHE_ERR_ALIGN;
     if (B == 0) return D2MHE_OK;
-    if ((uint64_t)B * ctx->L > 65535u && ctx->log2n > 14) return D2MHE_ERR_RANGE;
+    if ((uint64_t)B * ctx->L > 0x7fffffffull) return D2MHE_ERR_RANGE;
     return launch_ntt(ctx, polys, B, true, (hipStream_t)stream);
 }
 
@@ -347,7 +351,7 @@ d2mhe_status d2mhe_ntt_inverse(d2mhe_ctx *ctx, uint64_t *polys, uint32_t B, void
     if (!ctx || !polys) return D2MHE_ERR_NULL;
     if (misaligned(polys)) return D2MHE_ERR_ALIGN;
     if (B == 0) return D2MHE_OK;
-    if ((uint64_t)B * ctx->L > 65535u && ctx->log2n > 14) return D2MHE_ERR_RANGE;
+    if ((uint64_t)B * ctx->L > 0x7fffffffull) return D2MHE_ERR_RANGE;
     return launch_ntt(ctx, polys, B, false, (hipStream_t)stream);
 }
 

@@ -16,19 +16,28 @@ struct Launch {
                 hipLaunchKernelGGL(k_ntt_inverse<ENG>, dim3(polys_n), dim3(ENG::T), 0, st, polys, ctx->d_tabs, L);
             D2_LAUNCHED(ctx);
         } else {
-            // head: top stages across blocks; tail: one workgroup per block
+            // head: top stages across blocks; tail: one workgroup per block.  The batch is walked in
+            // chunks of polynomials that fit the second grid dimension.
             constexpr int LOGN = ENG::LOGN, LOGH = LOGN - ENG::LOGB;
-            dim3 hgrid((1u << (LOGN - LOGH)) / 256, polys_n), tgrid(1u << LOGH, polys_n);
-            if (forward) {
-                hipLaunchKernelGGL((k_head_forward<typename ENG::A, LOGN, LOGH>), hgrid, dim3(256), 0, st, polys, ctx->d_tabs, L);
+            const uint32_t chunk_polys = ctx->ntt_chunk_polys ? ctx->ntt_chunk_polys : polys_n;
+            for (uint32_t p0 = 0; p0 < polys_n; p0 += chunk_polys) {
+                const uint32_t n = polys_n - p0 < chunk_polys ? polys_n - p0 : chunk_polys;
+                uint64_t *base = polys + ((size_t)p0 << LOGN);
+                // limb of polynomial p = (p0 + p) % L: pass the offset so that the kernels see it
+                dim3 hgrid((1u << (LOGN - LOGH)) / 256, n), tgrid(1u << LOGH, n);
+                if (forward) {
+                    hipLaunchKernelGGL((k_head_forward<typename ENG::A, LOGN, LOGH>), hgrid, dim3(256), 0, st, base,
+                                       ctx->d_tabs, L, p0);
+                    D2_LAUNCHED(ctx);
+                    hipLaunchKernelGGL(k_tail_forward<ENG>, tgrid, dim3(ENG::T), 0, st, base, ctx->d_tabs, L, p0);
+                } else {
+                    hipLaunchKernelGGL(k_tail_inverse<ENG>, tgrid, dim3(ENG::T), 0, st, base, ctx->d_tabs, L, p0);
+                    D2_LAUNCHED(ctx);
+                    hipLaunchKernelGGL((k_head_inverse<typename ENG::A, LOGN, LOGH>), hgrid, dim3(256), 0, st, base,
+                                       ctx->d_tabs, L, p0);
+                }
                 D2_LAUNCHED(ctx);
-                hipLaunchKernelGGL(k_tail_forward<ENG>, tgrid, dim3(ENG::T), 0, st, polys, ctx->d_tabs, L);
-            } else {
-                hipLaunchKernelGGL(k_tail_inverse<ENG>, tgrid, dim3(ENG::T), 0, st, polys, ctx->d_tabs, L);
-                D2_LAUNCHED(ctx);
-                hipLaunchKernelGGL((k_head_inverse<typename ENG::A, LOGN, LOGH>), hgrid, dim3(256), 0, st, polys, ctx->d_tabs, L);
             }
-            D2_LAUNCHED(ctx);
         }
         return D2MHE_OK;
     }

@@ -4,7 +4,7 @@
 namespace d2 {
 const EngineOps *ops_b_12()
 {
-    static const EngineOps ops = Launch<Engine<ArithB, 12, 4>>::full();
+    static const EngineOps ops = Launch<Engine<ArithB, 12, 3>>::full();
     return &ops;
 }
 }

@@ -4,7 +4,7 @@
 namespace d2 {
 const EngineOps *ops_f_12()
 {
-    static const EngineOps ops = Launch<Engine<ArithF, 12, 4>>::full();
+    static const EngineOps ops = Launch<Engine<ArithF, 12, 3>>::full();
     return &ops;
 }
 }

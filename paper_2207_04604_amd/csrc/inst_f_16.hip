@@ -4,7 +4,7 @@
 namespace d2 {
 const EngineOps *ops_f_16()
 {
-    static const EngineOps ops = Launch<Engine<ArithF, 16, 4, 12>>::transforms_only();
+    static const EngineOps ops = Launch<Engine<ArithF, 16, 3, 12>>::transforms_only();
     return &ops;
 }
 }

@@ -4,7 +4,7 @@
 namespace d2 {
 const EngineOps *ops_s_12()
 {
-    static const EngineOps ops = Launch<Engine<ArithS, 12, 4>>::full();
+    static const EngineOps ops = Launch<Engine<ArithS, 12, 3>>::full();
     return &ops;
 }
 }

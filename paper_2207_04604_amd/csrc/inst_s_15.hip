@@ -4,7 +4,7 @@
 namespace d2 {
 const EngineOps *ops_s_15()
 {
-    static const EngineOps ops = Launch<Engine<ArithS, 15, 4, 12>>::transforms_only();
+    static const EngineOps ops = Launch<Engine<ArithS, 15, 3, 12>>::transforms_only();
     return &ops;
 }
 }

@@ -4,7 +4,7 @@
 namespace d2 {
 const EngineOps *ops_s_16()
 {
-    static const EngineOps ops = Launch<Engine<ArithS, 16, 4, 12>>::transforms_only();
+    static const EngineOps ops = Launch<Engine<ArithS, 16, 3, 12>>::transforms_only();
     return &ops;
 }
 }

@@ -158,12 +158,13 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_ntt_inverse(uint64_t *po
 // Between the two kernels the data stays in the policy's lazy representation.
 // -------------------------------------------------------------------------------------
 template <class A, int LOGN, int LOGH>
-__global__ void __launch_bounds__(256) k_head_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L)
+__global__ void __launch_bounds__(256) k_head_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L,
+                                                        uint32_t poly0)
 {
     constexpr int H = 1 << LOGH;
     constexpr int STRIDE = 1 << (LOGN - LOGH);
     const uint32_t poly = blockIdx.y;
-    const LimbTab &tb = tabs[poly % L];
+    const LimbTab &tb = tabs[(poly0 + poly) % L];
     const typename A::Mod md = A::mod(tb.q, tb.one_s);
     const Tw *tw = tb.fwd;
     uint64_t *p = polys + ((size_t)poly << LOGN) + (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -188,12 +189,13 @@ __global__ void __launch_bounds__(256) k_head_forward(uint64_t *polys, const Lim
 }
 
 template <class A, int LOGN, int LOGH>
-__global__ void __launch_bounds__(256) k_head_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L)
+__global__ void __launch_bounds__(256) k_head_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L,
+                                                        uint32_t poly0)
 {
     constexpr int H = 1 << LOGH;
     constexpr int STRIDE = 1 << (LOGN - LOGH);
     const uint32_t poly = blockIdx.y;
-    const LimbTab &tb = tabs[poly % L];
+    const LimbTab &tb = tabs[(poly0 + poly) % L];
     const typename A::Mod md = A::mod(tb.q, tb.one_s);
     const Tw *tw = tb.inv;
     uint64_t *p = polys + ((size_t)poly << LOGN) + (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -227,13 +229,14 @@ __global__ void __launch_bounds__(256) k_head_inverse(uint64_t *polys, const Lim
 
 // tail: grid.x = blocks per polynomial, grid.y = polynomial index (b * L + limb)
 template <class ENG>
-__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L)
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L,
+                                                        uint32_t poly0)
 {
     typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
     const uint32_t poly = blockIdx.y, blk = blockIdx.x;
-    const LimbTab &tb = tabs[poly % L];
+    const LimbTab &tb = tabs[(poly0 + poly) % L];
     const typename A::Mod md = A::mod(tb.q, tb.one_s);
     uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
     typename A::elem x[ENG::E];
@@ -245,13 +248,14 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_forward(uint64_t *p
 }
 
 template <class ENG>
-__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L)
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L,
+                                                        uint32_t poly0)
 {
     typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
     const uint32_t poly = blockIdx.y, blk = blockIdx.x;
-    const LimbTab &tb = tabs[poly % L];
+    const LimbTab &tb = tabs[(poly0 + poly) % L];
     const typename A::Mod md = A::mod(tb.q, tb.one_s);
     uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
     typename A::elem x[ENG::E];

@@ -168,6 +168,30 @@ struct Engine {
         }
     }
 
+    // Passes [PB, PE) only (forward order); ownership goes from pass PB to pass PE-1.
+    template <int PB, int PE>
+    D2_DEV static void forward_range(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
+                                     const Mod &md)
+    {
+        fwd_pass<PB>(x, tid, blk, tw, md);
+        if constexpr (PB + 1 < PE) {
+            exchange<PB, PB + 1>(x, lds, tid);
+            forward_range<PB + 1, PE>(x, lds, tid, blk, tw, md);
+        }
+    }
+
+    // Passes PE-1 down to PB (inverse order); ownership goes from pass PE-1 to pass PB.
+    template <int PB, int PE, bool FOLD>
+    D2_DEV static void inverse_range(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
+                                     const Mod &md, const Twid &ninv, const Twid &wn)
+    {
+        inv_pass<PE - 1, FOLD>(x, tid, blk, tw, md, ninv, wn);
+        if constexpr (PE - 1 > PB) {
+            exchange<PE - 1, PE - 2>(x, lds, tid);
+            inverse_range<PB, PE - 1, FOLD>(x, lds, tid, blk, tw, md, ninv, wn);
+        }
+    }
+
     // x: pass-0 ownership (policy's forward input range) -> last-pass ownership, lazy.
     D2_DEV static void forward(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
                                const Mod &md)
