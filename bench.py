@@ -39,6 +39,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-ntt", action="store_true", help="skip the transform micro-benchmark")
     ap.add_argument("--ntt-reps", type=int, default=20)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run plain device copies of 512 MiB (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (all parties are simulated on one device); "
@@ -54,6 +56,22 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     dev = torch.device("cuda:0")
+    if args.calibrate_copy:
+        src = torch.zeros(512 * 1024 * 1024 // 8, dtype=torch.int64, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        for _ in range(10):
+            dst.copy_(src)
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[1]) / 10
+        print(json.dumps({"copy_bytes_read": src.numel() * 8, "copy_bytes_written": src.numel() * 8, "ms": ms,
+                          "GB_per_s": 2 * src.numel() * 8 / ms / 1e6}))
+        return
     stream = torch.cuda.current_stream()
     sptr = stream.cuda_stream
 

@@ -24,14 +24,14 @@ struct Launch {
                 const uint32_t n = polys_n - p0 < chunk_polys ? polys_n - p0 : chunk_polys;
                 uint64_t *base = polys + ((size_t)p0 << LOGN);
                 // limb of polynomial p = (p0 + p) % L: pass the offset so that the kernels see it
-                dim3 hgrid((1u << (LOGN - LOGH)) / 256, n), tgrid(1u << LOGH, n);
+                dim3 hgrid((1u << (LOGN - LOGH)) / 256, n), tgrid((1u << LOGH) * n);
                 if (forward) {
                     hipLaunchKernelGGL((k_head_forward<typename ENG::A, LOGN, LOGH>), hgrid, dim3(256), 0, st, base,
                                        ctx->d_tabs, L, p0);
                     D2_LAUNCHED(ctx);
-                    hipLaunchKernelGGL(k_tail_forward<ENG>, tgrid, dim3(ENG::T), 0, st, base, ctx->d_tabs, L, p0);
+                    hipLaunchKernelGGL(k_tail_forward<ENG>, tgrid, dim3(ENG::T), 0, st, base, ctx->d_tabs, L, p0, n);
                 } else {
-                    hipLaunchKernelGGL(k_tail_inverse<ENG>, tgrid, dim3(ENG::T), 0, st, base, ctx->d_tabs, L, p0);
+                    hipLaunchKernelGGL(k_tail_inverse<ENG>, tgrid, dim3(ENG::T), 0, st, base, ctx->d_tabs, L, p0, n);
                     D2_LAUNCHED(ctx);
                     hipLaunchKernelGGL((k_head_inverse<typename ENG::A, LOGN, LOGH>), hgrid, dim3(256), 0, st, base,
                                        ctx->d_tabs, L, p0);

@@ -227,15 +227,42 @@ __global__ void __launch_bounds__(256) k_head_inverse(uint64_t *polys, const Lim
     for (int k = 0; k < H; ++k) p[(size_t)k * STRIDE] = A::canon_inv(x[k], md);
 }
 
-// tail: grid.x = blocks per polynomial, grid.y = polynomial index (b * L + limb)
+// Tiles that share twiddles -- the same (limb, block) of every polynomial of the batch -- should
+// run back to back on the same XCD, whose L2 then serves the 64 KB of twiddles to all of them
+// (workgroups are handed to the 8 XCDs round-robin by linear id).  Launch order i -> slot:
+// XCD x = i % 8 walks the contiguous slot range [x * total/8, (x+1) * total/8); slot -> (group =
+// limb * blocks + block, member = batch index).  Returns the polynomial index (b * L + limb)
+// within this launch and the block.
+D2_DEV void tail_tile(uint32_t i, uint32_t total, uint32_t polys, uint32_t L, uint32_t nblk, uint32_t poly0,
+                      uint32_t &poly, uint32_t &blk)
+{
+    uint32_t slot = i;
+    if ((total & 7u) == 0) slot = (i & 7u) * (total >> 3) + (i >> 3);
+    // members of a group: polynomials of this launch with the same limb
+    const uint32_t B = polys / L;                 // whole batches in this launch (polys = B * L + rest)
+    const uint32_t grouped = B * L * nblk;        // slots covered by whole batches
+    if (B == 0 || slot >= grouped) {              // leftovers: plain order
+        poly = slot / nblk;
+        blk = slot % nblk;
+        return;
+    }
+    const uint32_t group = slot / B, member = slot % B;
+    const uint32_t limb_pos = group / nblk;       // position of the limb inside a batch of this launch
+    blk = group % nblk;
+    poly = member * L + limb_pos;
+    (void)poly0;
+}
+
+// tail: 1-D grid over (polynomial, block) tiles, see tail_tile
 template <class ENG>
 __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L,
-                                                        uint32_t poly0)
+                                                        uint32_t poly0, uint32_t npolys)
 {
     typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
-    const uint32_t poly = blockIdx.y, blk = blockIdx.x;
+    uint32_t poly, blk;
+    tail_tile(blockIdx.x, gridDim.x, npolys, L, 1u << (ENG::LOGN - ENG::LOGB), poly0, poly, blk);
     const LimbTab &tb = tabs[(poly0 + poly) % L];
     const typename A::Mod md = A::mod(tb.q, tb.one_s);
     uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
@@ -249,12 +276,13 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_forward(uint64_t *p
 
 template <class ENG>
 __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L,
-                                                        uint32_t poly0)
+                                                        uint32_t poly0, uint32_t npolys)
 {
     typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
-    const uint32_t poly = blockIdx.y, blk = blockIdx.x;
+    uint32_t poly, blk;
+    tail_tile(blockIdx.x, gridDim.x, npolys, L, 1u << (ENG::LOGN - ENG::LOGB), poly0, poly, blk);
     const LimbTab &tb = tabs[(poly0 + poly) % L];
     const typename A::Mod md = A::mod(tb.q, tb.one_s);
     uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
@@ -482,15 +510,17 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
         const uint64_t *p0 = pk + off, *p0s = pk + LN + off;
         const uint64_t *p1 = pk + 2 * LN + off, *p1s = pk + 3 * LN + off;
         const int tl = opaque(tid);
-        // NTT(mu) is parked (lazy, as raw bits) in the c1 slot of the output, which every thread
-        // re-reads at its own positions and overwrites last; keeping it in registers across the
-        // next two transforms would cost 2 E registers and halve the occupancy.
+        // With 16 coefficients per thread NTT(mu) is parked (lazy, as raw bits) in the c1 slot of the
+        // output, which every thread re-reads at its own positions and overwrites last: keeping
+        // it in 32 registers across the next two transforms would halve the occupancy.  With 8
+        // per thread it stays in registers (no extra memory traffic).
+        constexpr bool STASH = E > 8;
         uint64_t *stash = out + LN + off;
-        {
-            elem u[E];
+        elem u[E];
 #pragma unroll
-            for (int k = 0; k < E; ++k) u[k] = A::from_small(sbyte(opaque(smp[k]), 0), md);
-            ENG::forward(u, lds, tl, 0, opaque(tb.fwd), md);
+        for (int k = 0; k < E; ++k) u[k] = A::from_small(sbyte(opaque(smp[k]), 0), md);
+        ENG::forward(u, lds, tl, 0, opaque(tb.fwd), md);
+        if (STASH) {
 #pragma unroll
             for (int k = 0; k < E; ++k) st64(stash, 8u * (uint32_t)tl, 8u * ENG::T * k, to_bits<A>(u[k]));
         }
@@ -503,9 +533,9 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
 #pragma unroll
         for (int k = 0; k < E; ++k) {
             const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
-            const elem u = from_bits<A>(ld64(stash, lo, so));
+            const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k];
             st64(out + off, lo, so,
-                 A::canon_acc(A::add(A::mul(u, A::tw(ld64(p0, lo, so), ld64(p0s, lo, so)), md), x[k]), md));
+                 A::canon_acc(A::add(A::mul(uu, A::tw(ld64(p0, lo, so), ld64(p0s, lo, so)), md), x[k]), md));
         }
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(opaque(smp[k]), 2), md);
@@ -513,9 +543,9 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
 #pragma unroll
         for (int k = 0; k < E; ++k) {
             const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
-            const elem u = from_bits<A>(ld64(stash, lo, so));
+            const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k];
             st64(stash, lo, so,
-                 A::canon_acc(A::add(A::mul(u, A::tw(ld64(p1, lo, so), ld64(p1s, lo, so)), md), x[k]), md));
+                 A::canon_acc(A::add(A::mul(uu, A::tw(ld64(p1, lo, so), ld64(p1s, lo, so)), md), x[k]), md));
         }
     }
 }

@@ -120,30 +120,37 @@ struct Engine {
         }
     }
 
-    // LDS word of register slot k of thread tid in pass P = slot_base<P>(tid) + slot_off<P>(k):
-    // the thread bits and the slot bits of an index are disjoint, so the padded address splits
-    // into a per-thread base and a compile-time offset (an instruction immediate).
-    template <int P>
-    D2_DEV static int slot_base(int tid) { return phys(index_of<P>(0, tid)); }
-    template <int P>
-    static constexpr int slot_off(int k)
+    // LDS layout of an exchange between passes P and P+1 (either direction): one run of 2^W pad
+    // words after every 2^(W + ELOG) coefficients, W = window base of pass P+1.  The side with the
+    // large window touches runs of >= 32 consecutive words, the side with the small window walks
+    // with a stride that the padding turns into 2^W (mod 32 words): both are conflict-free for
+    // 8-byte accesses on 64 four-byte banks, 32 lanes per cycle pair.
+    template <int X>   // X = the later pass of the pair
+    D2_DEV static constexpr int phys_x(int idx)
     {
-        constexpr int wb = wbase(P);
-        return (k << wb) + ((k << wb) >> ELOG);
+        constexpr int W = wbase(X);
+        return idx + ((idx >> (W + ELOG)) << W);
     }
+    // word of register slot k of thread tid in pass P = per-thread base + compile-time offset
+    // (thread bits and slot bits of an index are disjoint, so the padded address splits).
+    template <int P, int X>
+    D2_DEV static int slot_base(int tid) { return phys_x<X>(index_of<P>(0, tid)); }
+    template <int P, int X>
+    static constexpr int slot_off(int k) { return phys_x<X>(k << wbase(P)); }
 
     // Hand the coefficients from the owners of pass PF to the owners of pass PT.
     template <int PF, int PT>
     D2_DEV static void exchange(elem (&x)[E], uint64_t *lds, int tid)
     {
-        uint64_t *wr = lds + slot_base<PF>(tid);
-        const uint64_t *rd = lds + slot_base<PT>(tid);
+        constexpr int X = PF > PT ? PF : PT;
+        uint64_t *wr = lds + slot_base<PF, X>(tid);
+        const uint64_t *rd = lds + slot_base<PT, X>(tid);
         __syncthreads();                       // earlier readers of lds are done
 #pragma unroll
-        for (int k = 0; k < E; ++k) wr[slot_off<PF>(k)] = to_bits<A>(x[k]);
+        for (int k = 0; k < E; ++k) wr[slot_off<PF, X>(k)] = to_bits<A>(x[k]);
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = from_bits<A>(rd[slot_off<PT>(k)]);
+        for (int k = 0; k < E; ++k) x[k] = from_bits<A>(rd[slot_off<PT, X>(k)]);
     }
 
     template <int P>
