@@ -22,6 +22,12 @@ VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz = 39.3
 # VALU instructions of one butterfly in the minimal sequence of each arithmetic back-end
 # (csrc/arith.hpp): doubles for moduli < 2^44, 63-bit Shoup with an approximate quotient for
 # moduli < 2^55, exact Harvey butterflies for moduli < 2^61.
+# HBM bytes of one launch of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by
+# a plain 512 MiB device copy (profiles/k_encrypt_C2_round_and_ntt_C5.txt); only for the
+# workload that was profiled.
+MEASURED_TRAFFIC_BYTES = {"C2": 64.9e6 + 393.2e6}
+
+
 def ops_per_butterfly(qmax):
     if qmax < (1 << 44):
         return 8, "f64"
@@ -165,7 +171,9 @@ def main():
         "roofline": {"kernel": "k_encrypt (fused encode + encrypt)", "bound": "alu", "achieved": enc_op_rate,
                      "peak": VALU_PEAK_TOPS, "unit": f"T lane-ops/s (butterfly instructions, {OPB} per butterfly, {arith})",
                      "frac": enc_op_rate / VALU_PEAK_TOPS,
-                     "traffic": None, "avg_launch_ms": enc_ms,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if n_enc_launch == 1 else None,
+                     "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
+                     "algorithmic_bytes": enc_bytes, "avg_launch_ms": enc_ms,
                      "hbm_algorithmic_GB_per_s": enc_bytes / 1e9 / (enc_ms * 1e-3),
                      "hbm_frac": enc_bytes / 1e9 / (enc_ms * 1e-3) / HBM_PEAK_GBS},
     }
