@@ -6,7 +6,8 @@
 // passes of (up to) ELOG stages; during a pass a thread owns the E coefficients whose
 // index differs only in the ELOG-bit "window" of that pass, so all butterflies of the
 // pass are register-to-register.  Between passes the coefficients change owner through
-// LDS (write at the old owner, barrier, read at the new owner).
+// LDS (write at the old owner, barrier, read at the new owner); once the window base is 6 or less
+// both owners sit in the same wavefront and the barrier is dropped.
 //
 // Forward transform: merged Cooley-Tukey stages (the psi twist is folded into the
 // twiddles), natural-order input, stage s pairs indices that differ in bit LOGN-1-s and
@@ -25,7 +26,24 @@
 #pragma once
 #include "arith.hpp"
 
+#ifndef D2_HOST_WAVE_SYNC        // a host build that runs the kernels supplies its own
+#define D2_HOST_WAVE_SYNC() __syncthreads()
+#endif
+
 namespace d2 {
+
+// Order the LDS accesses of one wavefront: no instruction, only a point the compiler moves no
+// memory access across.
+D2_DEV void wave_sync()
+{
+#if D2_GCN_ASM
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#else
+    D2_HOST_WAVE_SYNC();
+#endif
+}
 
 template <class A_, int LOGN_, int ELOG_, int LOGB_ = LOGN_>
 struct Engine {
@@ -138,17 +156,26 @@ struct Engine {
     template <int P, int X>
     static constexpr int slot_off(int k) { return phys_x<X>(k << wbase(P)); }
 
+    // An exchange between two passes whose window bases are both <= 6 never leaves a wavefront:
+    // the wave of a coefficient is then index >> (ELOG + 6) on both sides, and because every
+    // exchange pads by the same ratio the words of wave v are [v, v + 1) * 64 * (E + 1) in all of
+    // them.  Such an exchange needs no workgroup barrier (LDS serves the instructions of one wave
+    // in order), only a guarantee that the compiler keeps the order.
+    template <int PF, int PT>
+    static constexpr bool intra_wave() { return wbase(PF < PT ? PF : PT) <= 6; }
+
     // Hand the coefficients from the owners of pass PF to the owners of pass PT.
     template <int PF, int PT>
     D2_DEV static void exchange(elem (&x)[E], uint64_t *lds, int tid)
     {
         constexpr int X = PF > PT ? PF : PT;
+        constexpr bool INTRA = intra_wave<PF, PT>();
         uint64_t *wr = lds + slot_base<PF, X>(tid);
         const uint64_t *rd = lds + slot_base<PT, X>(tid);
-        __syncthreads();                       // earlier readers of lds are done
+        if (INTRA) wave_sync(); else __syncthreads();      // earlier readers of these words are done
 #pragma unroll
         for (int k = 0; k < E; ++k) wr[slot_off<PF, X>(k)] = to_bits<A>(x[k]);
-        __syncthreads();
+        if (INTRA) wave_sync(); else __syncthreads();
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = from_bits<A>(rd[slot_off<PT, X>(k)]);
     }
@@ -175,31 +202,10 @@ struct Engine {
         }
     }
 
-    // Passes [PB, PE) only (forward order); ownership goes from pass PB to pass PE-1.
-    template <int PB, int PE>
-    D2_DEV static void forward_range(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
-                                     const Mod &md)
-    {
-        fwd_pass<PB>(x, tid, blk, tw, md);
-        if constexpr (PB + 1 < PE) {
-            exchange<PB, PB + 1>(x, lds, tid);
-            forward_range<PB + 1, PE>(x, lds, tid, blk, tw, md);
-        }
-    }
-
-    // Passes PE-1 down to PB (inverse order); ownership goes from pass PE-1 to pass PB.
-    template <int PB, int PE, bool FOLD>
-    D2_DEV static void inverse_range(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
-                                     const Mod &md, const Twid &ninv, const Twid &wn)
-    {
-        inv_pass<PE - 1, FOLD>(x, tid, blk, tw, md, ninv, wn);
-        if constexpr (PE - 1 > PB) {
-            exchange<PE - 1, PE - 2>(x, lds, tid);
-            inverse_range<PB, PE - 1, FOLD>(x, lds, tid, blk, tw, md, ninv, wn);
-        }
-    }
-
     // x: pass-0 ownership (policy's forward input range) -> last-pass ownership, lazy.
+    // LDS protocol of a workgroup: whoever writes words that other waves may still be reading
+    // puts a workgroup barrier in front of the write.  The first exchange of a forward transform
+    // is of that kind and has its barrier; later ones stay inside the wave.
     D2_DEV static void forward(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
                                const Mod &md)
     {
@@ -207,10 +213,16 @@ struct Engine {
     }
 
     // x: last-pass ownership (canonical input) -> pass-0 ownership, lazy; scaled by N^-1 when FOLD.
+    // The first exchange of an inverse transform stays inside the wave and therefore has no
+    // barrier of its own: the one here covers readers in other waves (of staged inputs, or of the
+    // last exchange of a preceding inverse transform).
     template <bool FOLD>
     D2_DEV static void inverse(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
                                const Mod &md, const Twid &ninv, const Twid &wn)
     {
+        if constexpr (NPASS > 1) {
+            if (intra_wave<NPASS - 1, NPASS - 2>()) __syncthreads();
+        }
         inv_from<NPASS - 1, FOLD>(x, lds, tid, blk, tw, md, ninv, wn);
     }
 };
