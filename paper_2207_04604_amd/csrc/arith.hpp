@@ -69,6 +69,72 @@ D2_DEV uint64_t csub(uint64_t x, uint64_t m)
 #endif
 }
 
+// ---------------------------------------------------------------------------------------
+// Global memory access.
+//   Per-lane: raw buffer instructions -- a wave-uniform base (descriptor in SGPRs) plus one 32-bit
+//   per-lane byte offset and a uniform offset.  Plain 64-bit addressing would hold a VGPR pair per
+//   array and slot, and generic pointers become flat instructions, whose completion is counted
+//   together with LDS traffic.  The ranges are < 4 GB from the base.
+//   Wave-uniform table reads: through the constant address space, which the compiler turns into
+//   scalar loads (results in SGPRs) when it can see that the offset is uniform.
+// ---------------------------------------------------------------------------------------
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+struct U128 {
+    uint64_t lo, hi;
+};
+D2_DEV uint64_t ld64(const void *base, uint32_t lane_off, uint32_t slot_off)
+{
+#if D2_GCN_ASM
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, 0xffffffff, 0x00020000);
+    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, lane_off, slot_off, 0);
+    return ((uint64_t)v.y << 32) | v.x;
+#else
+    return *(const uint64_t *)((const char *)base + lane_off + slot_off);
+#endif
+}
+D2_DEV U128 ld128(const void *base, uint32_t lane_off, uint32_t slot_off)
+{
+#if D2_GCN_ASM
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, 0xffffffff, 0x00020000);
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, slot_off, 0);
+    return U128{((uint64_t)v.y << 32) | v.x, ((uint64_t)v.w << 32) | v.z};
+#else
+    const uint64_t *p = (const uint64_t *)((const char *)base + lane_off + slot_off);
+    return U128{p[0], p[1]};
+#endif
+}
+D2_DEV void st64(void *base, uint32_t lane_off, uint32_t slot_off, uint64_t val)
+{
+#if D2_GCN_ASM
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(base, 0, 0xffffffff, 0x00020000);
+    u32x2 v;
+    v.x = (uint32_t)val;
+    v.y = (uint32_t)(val >> 32);
+    __builtin_amdgcn_raw_buffer_store_b64(v, r, lane_off, slot_off, 0);
+#else
+    *(uint64_t *)((char *)base + lane_off + slot_off) = val;
+#endif
+}
+D2_DEV uint64_t const_ld64(const void *base, uint32_t byte_off)
+{
+#if D2_GCN_ASM
+    typedef const __attribute__((address_space(4))) uint64_t *cptr;
+    return *(cptr)((uintptr_t)base + byte_off);
+#else
+    return *(const uint64_t *)((const char *)base + byte_off);
+#endif
+}
+// a value that is the same in every lane of the wavefront, moved to a scalar register
+D2_DEV uint32_t wave_uniform(uint32_t v)
+{
+#if D2_GCN_ASM
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
+#else
+    return v;
+#endif
+}
+
 // floor(w * 2^64 / q) for w < q < 2^61 by binary long division (set-up paths only).
 D2_DEV uint64_t shoup_quotient(uint64_t w, uint64_t q)
 {
@@ -193,7 +259,22 @@ struct ArithS {
     D2_DEV static Mod mod(uint64_t q, uint64_t one_s63) { return Mod{q, 0 - q, one_s63}; }
     D2_DEV static Twid tw(const Tw &t) { return Twid{t.w, t.ws}; }
     D2_DEV static Twid tw(uint64_t w, uint64_t ws64) { return Twid{w, ws64 >> 1}; }
-    D2_DEV static Twid load(const Tw *table, uint32_t i) { return tw(table[i]); }
+    // element of a prepared key: values at v, 64-bit quotients at vs
+    D2_DEV static Twid key(const uint64_t *v, const uint64_t *vs, uint32_t lane_off, uint32_t slot_off)
+    {
+        return tw(ld64(v, lane_off, slot_off), ld64(vs, lane_off, slot_off));
+    }
+    // table entry i: per-lane index / wave-uniform index
+    static constexpr bool SCALAR_TW = false;
+    D2_DEV static Twid load_v(const Tw *table, uint32_t i)
+    {
+        const U128 e = ld128(table, 16u * i, 0);
+        return Twid{e.lo, e.hi};
+    }
+    D2_DEV static Twid load_u(const Tw *table, uint32_t i)
+    {
+        return Twid{const_ld64(table, 16u * i), const_ld64(table, 16u * i + 8u)};
+    }
 
     // w*y mod q in [0, 4q), for y < 2^62.
     D2_DEV static elem mul(elem y, const Twid &w, const Mod &m)
@@ -260,7 +341,22 @@ struct ArithB {
     D2_DEV static Mod mod(uint64_t q, uint64_t one_s63) { return Mod{q, 0 - q, one_s63}; }
     D2_DEV static Twid tw(const Tw &t) { return Twid{t.w, t.ws}; }
     D2_DEV static Twid tw(uint64_t w, uint64_t ws64) { return Twid{w, ws64 >> 1}; }
-    D2_DEV static Twid load(const Tw *table, uint32_t i) { return tw(table[i]); }
+    // element of a prepared key: values at v, 64-bit quotients at vs
+    D2_DEV static Twid key(const uint64_t *v, const uint64_t *vs, uint32_t lane_off, uint32_t slot_off)
+    {
+        return tw(ld64(v, lane_off, slot_off), ld64(vs, lane_off, slot_off));
+    }
+    // table entry i: per-lane index / wave-uniform index
+    static constexpr bool SCALAR_TW = false;
+    D2_DEV static Twid load_v(const Tw *table, uint32_t i)
+    {
+        const U128 e = ld128(table, 16u * i, 0);
+        return Twid{e.lo, e.hi};
+    }
+    D2_DEV static Twid load_u(const Tw *table, uint32_t i)
+    {
+        return Twid{const_ld64(table, 16u * i), const_ld64(table, 16u * i + 8u)};
+    }
 
     // w*y mod q in [0, 2q), for y < 2^63.
     D2_DEV static elem mul(elem y, const Twid &w, const Mod &m)
@@ -344,7 +440,21 @@ struct ArithF {
     D2_DEV static Mod mod(uint64_t q, uint64_t) { return mod(q); }
     D2_DEV static Twid tw(const Tw &t) { return Twid{__longlong_as_double((long long)t.w)}; }
     D2_DEV static Twid tw(uint64_t w, uint64_t) { return Twid{u2d(w)}; }
-    D2_DEV static Twid load(const Tw *table, uint32_t i) { return Twid{((const double *)table)[2 * i]}; }
+    // element of a prepared key: only the values are read
+    D2_DEV static Twid key(const uint64_t *v, const uint64_t *, uint32_t lane_off, uint32_t slot_off)
+    {
+        return Twid{u2d(ld64(v, lane_off, slot_off))};
+    }
+    // table entry i: per-lane index / wave-uniform index (scalar registers feed the f64 ALU directly)
+    static constexpr bool SCALAR_TW = true;
+    D2_DEV static Twid load_v(const Tw *table, uint32_t i)
+    {
+        return Twid{__longlong_as_double((long long)ld64(table, 16u * i, 0))};
+    }
+    D2_DEV static Twid load_u(const Tw *table, uint32_t i)
+    {
+        return Twid{__longlong_as_double((long long)const_ld64(table, 16u * i))};
+    }
 
     // x - round(x/q) q: about (-q/2, q/2)
     D2_DEV static elem reduce(elem x, const Mod &m)

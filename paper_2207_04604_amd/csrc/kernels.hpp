@@ -3,6 +3,7 @@
 #pragma once
 #include "ntt_engine.hpp"
 #include "philox.hpp"
+#include <stddef.h>
 
 namespace d2 {
 
@@ -25,6 +26,25 @@ struct LimbTab {
     const Tw *fwd;      // forward twiddles, N entries
     const Tw *inv;      // inverse twiddles, N entries
 };
+
+// Entry i (uniform over the workgroup) of the table array, fetched with scalar loads so that the
+// constants and the table pointers stay in scalar registers.
+D2_DEV LimbTab load_tab(const LimbTab *tabs, uint32_t i)
+{
+    const LimbTab *e = tabs + i;
+    LimbTab r;
+    r.q = const_ld64(e, offsetof(LimbTab, q));
+    r.one_s = const_ld64(e, offsetof(LimbTab, one_s));
+    r.ninv = Tw{const_ld64(e, offsetof(LimbTab, ninv)), const_ld64(e, offsetof(LimbTab, ninv) + 8)};
+    r.wn = Tw{const_ld64(e, offsetof(LimbTab, wn)), const_ld64(e, offsetof(LimbTab, wn) + 8)};
+    r.lambda = Tw{const_ld64(e, offsetof(LimbTab, lambda)), const_ld64(e, offsetof(LimbTab, lambda) + 8)};
+    r.gamma = Tw{const_ld64(e, offsetof(LimbTab, gamma)), const_ld64(e, offsetof(LimbTab, gamma) + 8)};
+    r.theta_hi = const_ld64(e, offsetof(LimbTab, theta_hi));
+    r.theta_lo = const_ld64(e, offsetof(LimbTab, theta_lo));
+    r.fwd = (const Tw *)const_ld64(e, offsetof(LimbTab, fwd));
+    r.inv = (const Tw *)const_ld64(e, offsetof(LimbTab, inv));
+    return r;
+}
 
 struct RoundConst {
     uint64_t t;
@@ -65,34 +85,6 @@ struct GroupJobs {                     // one job = one group: K buffers laid ou
 
 D2_DEV uint32_t bitrev(uint32_t v, int bits) { return __brev(v) >> (32 - bits); }
 
-// Global accesses through raw buffer instructions: a wave-uniform base (descriptor in SGPRs),
-// one 32-bit per-lane byte offset shared by every array and register slot, and a uniform
-// offset per slot.  Plain 64-bit addressing would hold a VGPR pair per array and slot.
-// The ranges are < 4 GB from the base.
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-D2_DEV uint64_t ld64(const uint64_t *base, uint32_t lane_off, uint32_t slot_off)
-{
-#if D2_GCN_ASM
-    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, 0xffffffff, 0x00020000);
-    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, lane_off, slot_off, 0);
-    return ((uint64_t)v.y << 32) | v.x;
-#else
-    return *(const uint64_t *)((const char *)base + lane_off + slot_off);
-#endif
-}
-D2_DEV void st64(uint64_t *base, uint32_t lane_off, uint32_t slot_off, uint64_t val)
-{
-#if D2_GCN_ASM
-    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, 0xffffffff, 0x00020000);
-    u32x2 v;
-    v.x = (uint32_t)val;
-    v.y = (uint32_t)(val >> 32);
-    __builtin_amdgcn_raw_buffer_store_b64(v, r, lane_off, slot_off, 0);
-#else
-    *(uint64_t *)((char *)base + lane_off + slot_off) = val;
-#endif
-}
-
 // Returns v unchanged but opaque to the optimiser.  Used at the top of per-limb loops so that
 // per-thread addresses and sample conversions are recomputed per iteration (a few
 // instructions) instead of being hoisted and kept in ~100 registers across the whole loop.
@@ -104,15 +96,6 @@ D2_DEV int opaque(int v)
     return v;
 }
 D2_DEV uint32_t opaque(uint32_t v) { return (uint32_t)opaque((int)v); }
-// The same for a (wave-uniform) table pointer: two transforms in one loop body would otherwise
-// share their twiddle loads and keep all of them (~90 registers) alive from one to the next.
-D2_DEV const Tw *opaque(const Tw *p)
-{
-#if D2_GCN_ASM
-    asm volatile("" : "+v"(p));
-#endif
-    return p;
-}
 
 // -------------------------------------------------------------------------------------
 // Plain batched transforms: polys [B][L][N] in place, one workgroup per (b, limb).
@@ -123,7 +106,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_ntt_forward(uint64_t *po
     typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
-    const LimbTab &tb = tabs[blockIdx.x % L];
+    const LimbTab tb = load_tab(tabs, blockIdx.x % L);
     const typename A::Mod md = A::mod(tb.q, tb.one_s);
     uint64_t *p = polys + (size_t)blockIdx.x * ENG::NB;
     typename A::elem x[ENG::E];
@@ -140,7 +123,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_ntt_inverse(uint64_t *po
     typedef typename ENG::A A;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
-    const LimbTab &tb = tabs[blockIdx.x % L];
+    const LimbTab tb = load_tab(tabs, blockIdx.x % L);
     const typename A::Mod md = A::mod(tb.q, tb.one_s);
     uint64_t *p = polys + (size_t)blockIdx.x * ENG::NB;
     typename A::elem x[ENG::E];
@@ -164,7 +147,7 @@ __global__ void __launch_bounds__(256) k_head_forward(uint64_t *polys, const Lim
     constexpr int H = 1 << LOGH;
     constexpr int STRIDE = 1 << (LOGN - LOGH);
     const uint32_t poly = blockIdx.y;
-    const LimbTab &tb = tabs[(poly0 + poly) % L];
+    const LimbTab tb = load_tab(tabs, (poly0 + poly) % L);
     const typename A::Mod md = A::mod(tb.q, tb.one_s);
     const Tw *tw = tb.fwd;
     uint64_t *p = polys + ((size_t)poly << LOGN) + (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -176,7 +159,7 @@ __global__ void __launch_bounds__(256) k_head_forward(uint64_t *polys, const Lim
         const int s = LOGH - 1 - kb;
 #pragma unroll
         for (int g = 0; g < (H >> (kb + 1)); ++g) {
-            const typename A::Twid w = A::load(tw, (1u << s) + g);
+            const typename A::Twid w = load_tw_uniform<A>(tw, (1u << s) + g);
 #pragma unroll
             for (int j = 0; j < (1 << kb); ++j) {
                 const int k0 = (g << (kb + 1)) | j;
@@ -195,7 +178,7 @@ __global__ void __launch_bounds__(256) k_head_inverse(uint64_t *polys, const Lim
     constexpr int H = 1 << LOGH;
     constexpr int STRIDE = 1 << (LOGN - LOGH);
     const uint32_t poly = blockIdx.y;
-    const LimbTab &tb = tabs[(poly0 + poly) % L];
+    const LimbTab tb = load_tab(tabs, (poly0 + poly) % L);
     const typename A::Mod md = A::mod(tb.q, tb.one_s);
     const Tw *tw = tb.inv;
     uint64_t *p = polys + ((size_t)poly << LOGN) + (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -214,7 +197,7 @@ __global__ void __launch_bounds__(256) k_head_inverse(uint64_t *polys, const Lim
         } else {
 #pragma unroll
             for (int g = 0; g < (H >> (kb + 1)); ++g) {
-                const typename A::Twid w = A::load(tw, (1u << s) + g);
+                const typename A::Twid w = load_tw_uniform<A>(tw, (1u << s) + g);
 #pragma unroll
                 for (int j = 0; j < (1 << kb); ++j) {
                     const int k0 = (g << (kb + 1)) | j;
@@ -263,7 +246,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_forward(uint64_t *p
     const int tid = threadIdx.x;
     uint32_t poly, blk;
     tail_tile(blockIdx.x, gridDim.x, npolys, L, 1u << (ENG::LOGN - ENG::LOGB), poly0, poly, blk);
-    const LimbTab &tb = tabs[(poly0 + poly) % L];
+    const LimbTab tb = load_tab(tabs, (poly0 + poly) % L);
     const typename A::Mod md = A::mod(tb.q, tb.one_s);
     uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
     typename A::elem x[ENG::E];
@@ -283,7 +266,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_inverse(uint64_t *p
     const int tid = threadIdx.x;
     uint32_t poly, blk;
     tail_tile(blockIdx.x, gridDim.x, npolys, L, 1u << (ENG::LOGN - ENG::LOGB), poly0, poly, blk);
-    const LimbTab &tb = tabs[(poly0 + poly) % L];
+    const LimbTab tb = load_tab(tabs, (poly0 + poly) % L);
     const typename A::Mod md = A::mod(tb.q, tb.one_s);
     uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
     typename A::elem x[ENG::E];
@@ -399,7 +382,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encode(const float *grad
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
     uint32_t m[ENG::E];
-    encode_to_regs<ENG>(m, lds, tid, grad, (uint64_t)c * ENG::NB, n_values, tabs[rc.L], rc);
+    encode_to_regs<ENG>(m, lds, tid, grad, (uint64_t)c * ENG::NB, n_values, load_tab(tabs, rc.L), rc);
 #pragma unroll
     for (int k = 0; k < ENG::E; ++k) pt[(size_t)c * ENG::NB + ENG::coef_pos(k, tid)] = m[k];
 }
@@ -414,7 +397,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_decode(const uint64_t *p
     uint32_t m[ENG::E];
 #pragma unroll
     for (int k = 0; k < ENG::E; ++k) m[k] = (uint32_t)pt[(size_t)c * ENG::NB + ENG::coef_pos(k, tid)];
-    decode_from_regs<ENG>(m, lds, tid, out, (uint64_t)c * ENG::NB, n_values, tabs[rc.L], rc);
+    decode_from_regs<ENG>(m, lds, tid, out, (uint64_t)c * ENG::NB, n_values, load_tab(tabs, rc.L), rc);
 }
 
 // -------------------------------------------------------------------------------------
@@ -431,7 +414,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_keygen(uint32_t party, u
     uint32_t *lds32 = (uint32_t *)lds;
     const int tid = threadIdx.x;
     const uint32_t limb = blockIdx.x, L = rc.L;
-    const LimbTab &tb = tabs[limb];
+    const LimbTab tb = load_tab(tabs, limb);
     const uint64_t q = tb.q;
     const typename A::Mod md = A::mod(q, tb.one_s);
     const size_t LN = (size_t)L * ENG::NB, off = (size_t)limb * ENG::NB;
@@ -489,7 +472,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
 
     uint32_t m[E];
     if (FROM_FLOAT) {
-        encode_to_regs<ENG>(m, lds, tid, (const float *)jobs.src[job], (uint64_t)c * ENG::NB, n_values, tabs[L], rc);
+        encode_to_regs<ENG>(m, lds, tid, (const float *)jobs.src[job], (uint64_t)c * ENG::NB, n_values, load_tab(tabs, L), rc);
     } else {
         const uint64_t *pt = (const uint64_t *)jobs.src[job] + (size_t)c * ENG::NB;
 #pragma unroll
@@ -503,7 +486,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
     for (int k = 0; k < E; ++k) smp[k] = lds32[ENG::coef_pos(k, tid)];
 
     for (uint32_t limb = 0; limb < L; ++limb) {
-        const LimbTab &tb = tabs[limb];
+        const LimbTab tb = load_tab(tabs, limb);
         const typename A::Mod md = A::mod(tb.q, tb.one_s);
         const typename A::Twid lam = A::tw(tb.lambda);
         const size_t off = (size_t)limb * ENG::NB;
@@ -519,7 +502,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
         elem u[E];
 #pragma unroll
         for (int k = 0; k < E; ++k) u[k] = A::from_small(sbyte(opaque(smp[k]), 0), md);
-        ENG::forward(u, lds, tl, 0, opaque(tb.fwd), md);
+        ENG::forward(u, lds, tl, 0, tb.fwd, md);
         if (STASH) {
 #pragma unroll
             for (int k = 0; k < E; ++k) st64(stash, 8u * (uint32_t)tl, 8u * ENG::T * k, to_bits<A>(u[k]));
@@ -529,23 +512,28 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
         for (int k = 0; k < E; ++k)
             x[k] = A::add(A::mul(A::from_canon((uint64_t)opaque(m[k]), md), lam, md),
                           A::from_small(sbyte(opaque(smp[k]), 1), md));
-        ENG::forward(x, lds, opaque(tl), 0, opaque(tb.fwd), md);
+        ENG::forward(x, lds, opaque(tl), 0, tb.fwd, md);
+        // the key values are requested in one batch (a load placed after a store of the previous
+        // slot could not be moved in front of it)
+        typename A::Twid kv[E];
+#pragma unroll
+        for (int k = 0; k < E; ++k) kv[k] = A::key(p0, p0s, 8u * (uint32_t)tl, 8u * ENG::T * k);
 #pragma unroll
         for (int k = 0; k < E; ++k) {
             const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
             const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k];
-            st64(out + off, lo, so,
-                 A::canon_acc(A::add(A::mul(uu, A::tw(ld64(p0, lo, so), ld64(p0s, lo, so)), md), x[k]), md));
+            st64(out + off, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k]), md));
         }
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(opaque(smp[k]), 2), md);
-        ENG::forward(x, lds, opaque(tl), 0, opaque(tb.fwd), md);
+        ENG::forward(x, lds, opaque(tl), 0, tb.fwd, md);
+#pragma unroll
+        for (int k = 0; k < E; ++k) kv[k] = A::key(p1, p1s, 8u * (uint32_t)tl, 8u * ENG::T * k);
 #pragma unroll
         for (int k = 0; k < E; ++k) {
             const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
             const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k];
-            st64(stash, lo, so,
-                 A::canon_acc(A::add(A::mul(uu, A::tw(ld64(p1, lo, so), ld64(p1s, lo, so)), md), x[k]), md));
+            st64(stash, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k]), md));
         }
     }
 }
@@ -572,7 +560,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_share(ShareJobs jobs, ui
 #pragma unroll
     for (int k = 0; k < E; ++k) e[k] = (int)lds32[ENG::coef_pos(k, tid)];
     for (uint32_t limb = 0; limb < L; ++limb) {
-        const LimbTab &tb = tabs[limb];
+        const LimbTab tb = load_tab(tabs, limb);
         const typename A::Mod md = A::mod(tb.q, tb.one_s);
         const size_t off = (size_t)limb * ENG::NB;
         const int tl = opaque(tid);
@@ -580,11 +568,17 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_share(ShareJobs jobs, ui
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = A::from_small(opaque(e[k]), md);
         ENG::forward(x, lds, tl, 0, tb.fwd, md);
+        typename A::Twid kv[E];
+        uint64_t cv[E];
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            kv[k] = A::key(sk + off, sk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
+            cv[k] = ld64(c1 + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
+        }
 #pragma unroll
         for (int k = 0; k < E; ++k) {
             const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
-            const typename A::elem prod = A::mul(A::from_canon(ld64(c1 + off, lo, so), md),
-                                                 A::tw(ld64(sk + off, lo, so), ld64(sk + LN + off, lo, so)), md);
+            const typename A::elem prod = A::mul(A::from_canon(cv[k], md), kv[k], md);
             st64(out + off, lo, so, A::canon_acc(A::add(prod, x[k]), md));
         }
     }
@@ -611,7 +605,7 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
 #pragma unroll
     for (int k = 0; k < E; ++k) { acc_int[k] = 0; acc_frac[k] = 0; }
     for (uint32_t limb = 0; limb < L; ++limb) {
-        const LimbTab &tb = tabs[limb];
+        const LimbTab tb = load_tab(tabs, limb);
         const uint64_t q = tb.q;
         const typename A::Mod md = A::mod(q, tb.one_s);
         const size_t off = (size_t)limb * ENG::NB;
@@ -646,7 +640,7 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
 #pragma unroll
     for (int k = 0; k < E; ++k) m[k] = (uint32_t)((acc_int[k] + (acc_frac[k] >> 63)) % t);   // + 1/2, floor
     if (DECODE) {
-        decode_from_regs<ENG>(m, lds, tid, out, (uint64_t)c * ENG::NB, n_values, tabs[L], rc);
+        decode_from_regs<ENG>(m, lds, tid, out, (uint64_t)c * ENG::NB, n_values, load_tab(tabs, L), rc);
     } else {
 #pragma unroll
         for (int k = 0; k < E; ++k) pt[(size_t)c * ENG::NB + ENG::coef_pos(k, tid)] = m[k];

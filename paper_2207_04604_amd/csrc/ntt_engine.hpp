@@ -45,6 +45,14 @@ D2_DEV void wave_sync()
 #endif
 }
 
+// table entry with an index that is uniform over the workgroup
+template <class A>
+D2_DEV typename A::Twid load_tw_uniform(const Tw *tw, uint32_t i)
+{
+    if constexpr (A::SCALAR_TW) return A::load_u(tw, i);
+    else return A::load_v(tw, i);
+}
+
 template <class A_, int LOGN_, int ELOG_, int LOGB_ = LOGN_>
 struct Engine {
     typedef A_ A;
@@ -58,6 +66,11 @@ struct Engine {
     static constexpr int NPASS = (LOGB + ELOG - 1) / ELOG;
     static constexpr int LDS_WORDS = NB + (NB >> ELOG);   // one pad word per E coefficients
     static constexpr int WAVES = 4;   // waves per SIMD the kernels are compiled for (<= 128 VGPRs)
+#ifndef D2_TW_EARLY
+#define D2_TW_EARLY 0
+#endif
+    // next pass's twiddles requested before (true) or after (false) the butterflies of this pass
+    static constexpr bool TW_EARLY = D2_TW_EARLY;
 
     static_assert(LOGB >= ELOG && LOGB <= LOGN, "bad engine shape");
 
@@ -81,24 +94,54 @@ struct Engine {
     // position in natural (coefficient) order during pass 0
     D2_DEV static int coef_pos(int k, int tid) { return k * T + tid; }
 
+    // Twiddles of a pass: stage bit kb of the window uses E >> (kb + 1) consecutive table entries;
+    // they sit in slot (E >> (kb + 1)) - 1 + g of a per-pass array (E - 1 slots for a full window).
+    static constexpr int tw_slot(int kb, int g) { return (E >> (kb + 1)) - 1 + g; }
+    // With a window base of 6 or more all lanes of a wavefront use the same entries.
     template <int P>
-    D2_DEV static void fwd_pass(elem (&x)[E], int tid, uint32_t blk, const Tw *__restrict__ tw, const Mod &md)
+    static constexpr bool uniform_tw() { return A::SCALAR_TW && wbase(P) >= 6; }
+
+    // Fetch the twiddles of pass P (FOLD: the stage that multiplies by N^-1 takes none).  Issued
+    // one pass ahead of their use, so that the latency overlaps the butterflies and the exchange.
+    // DESC: requested in the order a forward pass uses them (highest stage bit first).
+    template <int P, bool FOLD, bool DESC>
+    D2_DEV static void load_tw(Twid (&w)[E], int tid, uint32_t blk, const Tw *tw)
     {
         constexpr int wb = wbase(P), lo = sbit(P), r = stages(P);
-        const uint32_t hi = (uint32_t)(tid >> wb);
+        uint32_t hi = (uint32_t)(tid >> wb);
+        // pass 0: T = 2^wb threads, nothing above the window.  Other uniform passes: taken from
+        // the hardware thread id, so that transforms sharing a table also share these loads.
+        if constexpr (wb == LOGB - ELOG) hi = 0;
+        else if constexpr (uniform_tw<P>()) hi = wave_uniform((uint32_t)threadIdx.x >> wb);
 #pragma unroll
-        for (int b = lo + r - 1; b >= lo; --b) {           // stage bit inside the block index
+        for (int i = 0; i < r; ++i) {
+            const int b = DESC ? lo + r - 1 - i : lo + i;  // stage bit inside the block index
             const int kb = b - wb;                         // bit inside the register slot
             const int s = LOGN - 1 - b;                    // stage number of the transform
+            if (FOLD && b == LOGN - 1) continue;
             // twiddle index = 2^s + (global index >> (b + 1))
             const uint32_t base = (1u << s) + (blk << (LOGB - b - 1)) + (hi << (ELOG - kb - 1));
 #pragma unroll
+            for (int g = 0; g < (E >> (kb + 1)); ++g) {
+                if constexpr (uniform_tw<P>()) w[tw_slot(kb, g)] = A::load_u(tw, base + g);
+                else w[tw_slot(kb, g)] = A::load_v(tw, base + g);
+            }
+        }
+    }
+
+    template <int P>
+    D2_DEV static void fwd_pass(elem (&x)[E], const Twid (&w)[E], const Mod &md)
+    {
+        constexpr int wb = wbase(P), lo = sbit(P), r = stages(P);
+#pragma unroll
+        for (int b = lo + r - 1; b >= lo; --b) {           // stage bit inside the block index
+            const int kb = b - wb;
+#pragma unroll
             for (int g = 0; g < (E >> (kb + 1)); ++g) {    // distinct twiddles of this stage
-                const Twid w = A::load(tw, base + g);
 #pragma unroll
                 for (int j = 0; j < (1 << kb); ++j) {
                     const int k0 = (g << (kb + 1)) | j;
-                    A::ct(x[k0], x[k0 | (1 << kb)], w, md);
+                    A::ct(x[k0], x[k0 | (1 << kb)], w[tw_slot(kb, g)], md);
                 }
             }
         }
@@ -107,11 +150,9 @@ struct Engine {
     // FOLD: this pass contains the last stage of the whole inverse transform (bit LOGN-1)
     // and multiplies by N^-1 there: ninv = N^-1, wn = (inverse twiddle 1) * N^-1.
     template <int P, bool FOLD>
-    D2_DEV static void inv_pass(elem (&x)[E], int tid, uint32_t blk, const Tw *__restrict__ tw, const Mod &md,
-                                const Twid &ninv, const Twid &wn)
+    D2_DEV static void inv_pass(elem (&x)[E], const Twid (&w)[E], const Mod &md, const Twid &ninv, const Twid &wn)
     {
         constexpr int wb = wbase(P), lo = sbit(P), r = stages(P);
-        const uint32_t hi = (uint32_t)(tid >> wb);
         if (P != NPASS - 1) {
 #pragma unroll
             for (int k = 0; k < E; ++k) A::inv_pass_begin(x[k], md);
@@ -119,19 +160,16 @@ struct Engine {
 #pragma unroll
         for (int b = lo; b < lo + r; ++b) {
             const int kb = b - wb;
-            const int s = LOGN - 1 - b;
-            const uint32_t base = (1u << s) + (blk << (LOGB - b - 1)) + (hi << (ELOG - kb - 1));
             if (FOLD && b == LOGN - 1) {
 #pragma unroll
                 for (int j = 0; j < (1 << kb); ++j) A::gs_last(x[j], x[j | (1 << kb)], ninv, wn, md);
             } else {
 #pragma unroll
                 for (int g = 0; g < (E >> (kb + 1)); ++g) {
-                    const Twid w = A::load(tw, base + g);
 #pragma unroll
                     for (int j = 0; j < (1 << kb); ++j) {
                         const int k0 = (g << (kb + 1)) | j;
-                        A::gs(x[k0], x[k0 | (1 << kb)], w, md);
+                        A::gs(x[k0], x[k0 | (1 << kb)], w[tw_slot(kb, g)], md);
                     }
                 }
             }
@@ -181,24 +219,34 @@ struct Engine {
     }
 
     template <int P>
-    D2_DEV static void fwd_from(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
-                                const Mod &md)
+    D2_DEV static void fwd_from(elem (&x)[E], const Twid (&w)[E], uint64_t *lds, int tid, uint32_t blk,
+                                const Tw *tw, const Mod &md)
     {
-        fwd_pass<P>(x, tid, blk, tw, md);
         if constexpr (P + 1 < NPASS) {
+            Twid wn[E];
+            if (TW_EARLY) load_tw<P + 1, false, true>(wn, tid, blk, tw);
+            fwd_pass<P>(x, w, md);
+            if (!TW_EARLY) load_tw<P + 1, false, true>(wn, tid, blk, tw);
             exchange<P, P + 1>(x, lds, tid);
-            fwd_from<P + 1>(x, lds, tid, blk, tw, md);
+            fwd_from<P + 1>(x, wn, lds, tid, blk, tw, md);
+        } else {
+            fwd_pass<P>(x, w, md);
         }
     }
 
     template <int P, bool FOLD>
-    D2_DEV static void inv_from(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
-                                const Mod &md, const Twid &ninv, const Twid &wn)
+    D2_DEV static void inv_from(elem (&x)[E], const Twid (&w)[E], uint64_t *lds, int tid, uint32_t blk,
+                                const Tw *tw, const Mod &md, const Twid &ninv, const Twid &wn)
     {
-        inv_pass<P, FOLD>(x, tid, blk, tw, md, ninv, wn);
         if constexpr (P > 0) {
+            Twid wnext[E];
+            if (TW_EARLY) load_tw<P - 1, FOLD, false>(wnext, tid, blk, tw);
+            inv_pass<P, FOLD>(x, w, md, ninv, wn);
+            if (!TW_EARLY) load_tw<P - 1, FOLD, false>(wnext, tid, blk, tw);
             exchange<P, P - 1>(x, lds, tid);
-            inv_from<P - 1, FOLD>(x, lds, tid, blk, tw, md, ninv, wn);
+            inv_from<P - 1, FOLD>(x, wnext, lds, tid, blk, tw, md, ninv, wn);
+        } else {
+            inv_pass<P, FOLD>(x, w, md, ninv, wn);
         }
     }
 
@@ -206,10 +254,11 @@ struct Engine {
     // LDS protocol of a workgroup: whoever writes words that other waves may still be reading
     // puts a workgroup barrier in front of the write.  The first exchange of a forward transform
     // is of that kind and has its barrier; later ones stay inside the wave.
-    D2_DEV static void forward(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
-                               const Mod &md)
+    D2_DEV static void forward(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *tw, const Mod &md)
     {
-        fwd_from<0>(x, lds, tid, blk, tw, md);
+        Twid w[E];
+        load_tw<0, false, true>(w, tid, blk, tw);
+        fwd_from<0>(x, w, lds, tid, blk, tw, md);
     }
 
     // x: last-pass ownership (canonical input) -> pass-0 ownership, lazy; scaled by N^-1 when FOLD.
@@ -217,13 +266,15 @@ struct Engine {
     // barrier of its own: the one here covers readers in other waves (of staged inputs, or of the
     // last exchange of a preceding inverse transform).
     template <bool FOLD>
-    D2_DEV static void inverse(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *__restrict__ tw,
-                               const Mod &md, const Twid &ninv, const Twid &wn)
+    D2_DEV static void inverse(elem (&x)[E], uint64_t *lds, int tid, uint32_t blk, const Tw *tw, const Mod &md,
+                               const Twid &ninv, const Twid &wn)
     {
+        Twid w[E];
+        load_tw<NPASS - 1, FOLD, false>(w, tid, blk, tw);
         if constexpr (NPASS > 1) {
             if (intra_wave<NPASS - 1, NPASS - 2>()) __syncthreads();
         }
-        inv_from<NPASS - 1, FOLD>(x, lds, tid, blk, tw, md, ninv, wn);
+        inv_from<NPASS - 1, FOLD>(x, w, lds, tid, blk, tw, md, ninv, wn);
     }
 };
 
