@@ -437,7 +437,8 @@ struct ArithF {
         const double qd = u2d(q);
         return Mod{qd, 1.0 / qd, q};
     }
-    D2_DEV static Mod mod(uint64_t q, uint64_t) { return mod(q); }
+    // aux: bits of the double 1/q (what the per-modulus table holds for this policy)
+    D2_DEV static Mod mod(uint64_t q, uint64_t aux) { return Mod{u2d(q), __longlong_as_double((long long)aux), q}; }
     D2_DEV static Twid tw(const Tw &t) { return Twid{__longlong_as_double((long long)t.w)}; }
     D2_DEV static Twid tw(uint64_t w, uint64_t) { return Twid{u2d(w)}; }
     // element of a prepared key: only the values are read
@@ -499,12 +500,13 @@ struct ArithF {
     D2_DEV static void inv_pass_begin(elem &x, const Mod &m) { x = reduce(x, m); }
     D2_DEV static elem inv_input(uint64_t canon, const Mod &) { return u2d(canon); }
 
+    // |x| <= 32 q -> [0, q).  x/q is either an integer or at least 1/q > 2^-44 away from one; the
+    // computed quotient is off by less than 2^-47, so with a bias of 2^-46 floor() is exact and the
+    // remainder needs no correction.
     D2_DEV static uint64_t canon_wide(elem x, const Mod &m)
     {
-        double r = reduce(x, m);
-        r = r < 0.0 ? r + m.q : r;
-        r = r >= m.q ? r - m.q : r;
-        return d2u(r);
+        const double b = __builtin_floor(__builtin_fma(x, m.qinv, 0x1p-46));
+        return d2u(__builtin_fma(-b, m.q, x));
     }
     D2_DEV static uint64_t canon_lazy(elem x, const Mod &m) { return canon_wide(x, m); }
     D2_DEV static uint64_t canon_fwd(elem x, const Mod &m) { return canon_wide(x, m); }

@@ -249,7 +249,12 @@ d2mhe_status d2mhe_create(const d2mhe_params *p, void *dev_workspace, size_t byt
         for (size_t k = 0; k < N; ++k) inv[k] = h_entry(ar, pw[h_bitrev((uint32_t)k, (int)log2n)], m);
         LimbTab &tb = tabs[i < L ? i : L];
         tb.q = m;
-        tb.one_s = (uint64_t)(((u128)1 << 63) / m);
+        if (ar == 0) {
+            const double qinv = 1.0 / (double)m;
+            std::memcpy(&tb.one_s, &qinv, sizeof(qinv));
+        } else {
+            tb.one_s = (uint64_t)(((u128)1 << 63) / m);
+        }
         const uint64_t ninv = h_inv((uint64_t)N % m, m);
         tb.ninv = h_entry(ar, ninv, m);
         tb.wn = h_entry(ar, h_mul(pw[h_bitrev(1u, (int)log2n)], ninv, m), m);   // inverse twiddle 1 times N^-1

@@ -16,7 +16,7 @@ constexpr int MAX_GROUP = 64;
 // is always {w, floor(w 2^64/q)} (the scale-and-round step runs on canonical integers).
 struct LimbTab {
     uint64_t q;
-    uint64_t one_s;     // floor(2^63 / q)
+    uint64_t one_s;     // floor(2^63 / q); floating-point policy: bits of the double 1/q
     Tw ninv;            // N^-1 mod q
     Tw wn;              // (inverse twiddle 1) * N^-1 mod q
     Tw lambda;          // floor(Q/t) mod q
@@ -610,13 +610,27 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
         const typename A::Mod md = A::mod(q, tb.one_s);
         const size_t off = (size_t)limb * ENG::NB;
         const int tl = opaque(tid);
-        uint64_t y[E];
+        // c0 + sum of the shares; the next member's values are in flight while this one's are added
+        uint64_t y[E], hv[E];
 #pragma unroll
         for (int k = 0; k < E; ++k) y[k] = ld64(c0 + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
-        for (uint32_t j = 0; j < K; ++j) {
-            const uint64_t *h = share_of(j) + (size_t)c * LN + off;
+        if (K > 0) {
+            const uint64_t *h = share_of(0) + (size_t)c * LN + off;
 #pragma unroll
-            for (int k = 0; k < E; ++k) y[k] = add_mod(y[k], ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k), q);
+            for (int k = 0; k < E; ++k) hv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
+        }
+        for (uint32_t j = 0; j < K; ++j) {
+            uint64_t nv[E];
+            if (j + 1 < K) {
+                const uint64_t *h = share_of(j + 1) + (size_t)c * LN + off;
+#pragma unroll
+                for (int k = 0; k < E; ++k) nv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
+            }
+#pragma unroll
+            for (int k = 0; k < E; ++k) {
+                y[k] = add_mod(y[k], hv[k], q);
+                hv[k] = nv[k];
+            }
         }
         typename A::elem x[E];
 #pragma unroll
@@ -635,10 +649,19 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
             acc_frac[k] = nf;
         }
     }
-    const uint64_t t = rc.t;
+    // + 1/2, floor, mod t.  The sum is below (L + 1) t < 2^36: reduce it in doubles (exact on
+    // integers; the quotient estimate can be off by one in either direction).
+    const double td = (double)(uint32_t)rc.t, tinv = 1.0 / td;
     uint32_t m[E];
 #pragma unroll
-    for (int k = 0; k < E; ++k) m[k] = (uint32_t)((acc_int[k] + (acc_frac[k] >> 63)) % t);   // + 1/2, floor
+    for (int k = 0; k < E; ++k) {
+        const uint64_t v = acc_int[k] + (acc_frac[k] >> 63);
+        const double vd = (double)(uint32_t)v + 4294967296.0 * (double)(uint32_t)(v >> 32);
+        double r = __builtin_fma(-__builtin_floor(vd * tinv), td, vd);
+        r = r < 0.0 ? r + td : r;
+        r = r >= td ? r - td : r;
+        m[k] = (uint32_t)r;
+    }
     if (DECODE) {
         decode_from_regs<ENG>(m, lds, tid, out, (uint64_t)c * ENG::NB, n_values, load_tab(tabs, L), rc);
     } else {
