@@ -66,11 +66,6 @@ struct Engine {
     static constexpr int NPASS = (LOGB + ELOG - 1) / ELOG;
     static constexpr int LDS_WORDS = NB + (NB >> ELOG);   // one pad word per E coefficients
     static constexpr int WAVES = 4;   // waves per SIMD the kernels are compiled for (<= 128 VGPRs)
-#ifndef D2_TW_EARLY
-#define D2_TW_EARLY 0
-#endif
-    // next pass's twiddles requested before (true) or after (false) the butterflies of this pass
-    static constexpr bool TW_EARLY = D2_TW_EARLY;
 
     static_assert(LOGB >= ELOG && LOGB <= LOGN, "bad engine shape");
 
@@ -224,9 +219,8 @@ struct Engine {
     {
         if constexpr (P + 1 < NPASS) {
             Twid wn[E];
-            if (TW_EARLY) load_tw<P + 1, false, true>(wn, tid, blk, tw);
             fwd_pass<P>(x, w, md);
-            if (!TW_EARLY) load_tw<P + 1, false, true>(wn, tid, blk, tw);
+            load_tw<P + 1, false, true>(wn, tid, blk, tw);
             exchange<P, P + 1>(x, lds, tid);
             fwd_from<P + 1>(x, wn, lds, tid, blk, tw, md);
         } else {
@@ -240,9 +234,8 @@ struct Engine {
     {
         if constexpr (P > 0) {
             Twid wnext[E];
-            if (TW_EARLY) load_tw<P - 1, FOLD, false>(wnext, tid, blk, tw);
             inv_pass<P, FOLD>(x, w, md, ninv, wn);
-            if (!TW_EARLY) load_tw<P - 1, FOLD, false>(wnext, tid, blk, tw);
+            load_tw<P - 1, FOLD, false>(wnext, tid, blk, tw);
             exchange<P, P - 1>(x, lds, tid);
             inv_from<P - 1, FOLD>(x, wnext, lds, tid, blk, tw, md, ninv, wn);
         } else {
