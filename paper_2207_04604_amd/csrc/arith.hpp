@@ -163,22 +163,27 @@ struct TwU {        // multiplicand and its 63-bit Shoup quotient
 // w*y - qh*q mod 2^64, written as w*y + qh*(2^64 - q) so that every term is added:
 // a chain of four 64-bit multiply-adds for the cross terms (only its low word matters; it is
 // shifted up by 32), then two more for the low x low terms on top of it.
+// SC: w sits in scalar registers (a multiplicand shared by the whole wavefront).
+#define D2_SHOUP_TAIL_ASM(WC)                                                                      \
+    asm("v_mad_u64_u32 %1, vcc, %4, %3, 0\n\t"                                                     \
+        "v_mad_u64_u32 %1, vcc, %5, %2, %1\n\t"                                                    \
+        "v_mad_u64_u32 %1, vcc, %6, %9, %1\n\t"                                                    \
+        "v_mad_u64_u32 %1, vcc, %7, %8, %1\n\t"                                                    \
+        "v_lshlrev_b64 %1, 32, %1\n\t"                                                             \
+        "v_mad_u64_u32 %0, vcc, %4, %2, %1\n\t"                                                    \
+        "v_mad_u64_u32 %0, vcc, %6, %8, %0"                                                        \
+        : "=&v"(acc), "=&v"(cross)                                                                 \
+        : "v"(y0), "v"(y1), WC(w0), WC(w1), "v"(h0), "v"(h1), "v"(n0), "v"(n1)                     \
+        : "vcc")
+template <bool SC = false>
 D2_DEV uint64_t shoup_tail(uint64_t y, uint64_t w, uint64_t qh, uint64_t nq)
 {
     const uint32_t y0 = lo32(y), y1 = hi32(y), w0 = lo32(w), w1 = hi32(w);
     const uint32_t h0 = lo32(qh), h1 = hi32(qh), n0 = lo32(nq), n1 = hi32(nq);
 #if D2_GCN_ASM
     uint64_t acc, cross;
-    asm("v_mad_u64_u32 %1, vcc, %4, %3, 0\n\t"
-        "v_mad_u64_u32 %1, vcc, %5, %2, %1\n\t"
-        "v_mad_u64_u32 %1, vcc, %6, %9, %1\n\t"
-        "v_mad_u64_u32 %1, vcc, %7, %8, %1\n\t"
-        "v_lshlrev_b64 %1, 32, %1\n\t"
-        "v_mad_u64_u32 %0, vcc, %4, %2, %1\n\t"
-        "v_mad_u64_u32 %0, vcc, %6, %8, %0"
-        : "=&v"(acc), "=&v"(cross)
-        : "v"(y0), "v"(y1), "v"(w0), "v"(w1), "v"(h0), "v"(h1), "v"(n0), "v"(n1)
-        : "vcc");
+    if constexpr (SC) D2_SHOUP_TAIL_ASM("s");
+    else D2_SHOUP_TAIL_ASM("v");
     return acc;
 #else
     uint64_t acc = mul32(w0, y0);
@@ -199,19 +204,23 @@ D2_DEV uint64_t shoup_tail_one(uint64_t y, uint64_t qh, uint64_t nq)
 
 // floor(ws*y / 2^63) up to an error of 2 (too small): drops the low x low partial product.
 // Needs ws < 2^63 and y < 2^63 (then the middle sum cannot overflow).
+#define D2_QHAT_APPROX_ASM(WC)                                                                     \
+    asm("v_mad_u64_u32 %0, vcc, %5, %2, 0\n\t"                                                     \
+        "v_mad_u64_u32 %1, vcc, %5, %3, 0\n\t"                                                     \
+        "v_mad_u64_u32 %0, vcc, %4, %3, %0\n\t"                                                    \
+        "v_lshrrev_b64 %0, 31, %0\n\t"                                                             \
+        "v_lshl_add_u64 %0, %1, 1, %0"                                                             \
+        : "=&v"(mid), "=&v"(top)                                                                   \
+        : "v"(y0), "v"(y1), WC(s0), WC(s1)                                                         \
+        : "vcc")
+template <bool SC = false>
 D2_DEV uint64_t qhat_approx(uint64_t y, uint64_t ws)
 {
     const uint32_t y0 = lo32(y), y1 = hi32(y), s0 = lo32(ws), s1 = hi32(ws);
 #if D2_GCN_ASM
     uint64_t mid, top;
-    asm("v_mad_u64_u32 %0, vcc, %5, %2, 0\n\t"
-        "v_mad_u64_u32 %1, vcc, %5, %3, 0\n\t"
-        "v_mad_u64_u32 %0, vcc, %4, %3, %0\n\t"
-        "v_lshrrev_b64 %0, 31, %0\n\t"
-        "v_lshl_add_u64 %0, %1, 1, %0"
-        : "=&v"(mid), "=&v"(top)
-        : "v"(y0), "v"(y1), "v"(s0), "v"(s1)
-        : "vcc");
+    if constexpr (SC) D2_QHAT_APPROX_ASM("s");
+    else D2_QHAT_APPROX_ASM("v");
     return mid;
 #else
     uint64_t mid = mul32(s1, y0);
@@ -222,21 +231,25 @@ D2_DEV uint64_t qhat_approx(uint64_t y, uint64_t ws)
 }
 
 // floor(ws*y / 2^63) exactly, for ws < 2^63 and y < 2^63.
+#define D2_QHAT_EXACT_ASM(WC)                                                                      \
+    asm("v_mad_u64_u32 %0, vcc, %4, %2, 0\n\t"                                                     \
+        "v_mad_u64_u32 %1, vcc, %5, %3, 0\n\t"                                                     \
+        "v_lshrrev_b64 %0, 32, %0\n\t"                                                             \
+        "v_mad_u64_u32 %0, vcc, %5, %2, %0\n\t"                                                    \
+        "v_mad_u64_u32 %0, vcc, %4, %3, %0\n\t"                                                    \
+        "v_lshrrev_b64 %0, 31, %0\n\t"                                                             \
+        "v_lshl_add_u64 %0, %1, 1, %0"                                                             \
+        : "=&v"(mid), "=&v"(top)                                                                   \
+        : "v"(y0), "v"(y1), WC(s0), WC(s1)                                                         \
+        : "vcc")
+template <bool SC = false>
 D2_DEV uint64_t qhat_exact(uint64_t y, uint64_t ws)
 {
     const uint32_t y0 = lo32(y), y1 = hi32(y), s0 = lo32(ws), s1 = hi32(ws);
 #if D2_GCN_ASM
     uint64_t mid, top;
-    asm("v_mad_u64_u32 %0, vcc, %4, %2, 0\n\t"
-        "v_mad_u64_u32 %1, vcc, %5, %3, 0\n\t"
-        "v_lshrrev_b64 %0, 32, %0\n\t"
-        "v_mad_u64_u32 %0, vcc, %5, %2, %0\n\t"
-        "v_mad_u64_u32 %0, vcc, %4, %3, %0\n\t"
-        "v_lshrrev_b64 %0, 31, %0\n\t"
-        "v_lshl_add_u64 %0, %1, 1, %0"
-        : "=&v"(mid), "=&v"(top)
-        : "v"(y0), "v"(y1), "v"(s0), "v"(s1)
-        : "vcc");
+    if constexpr (SC) D2_QHAT_EXACT_ASM("s");
+    else D2_QHAT_EXACT_ASM("v");
     return mid;
 #else
     uint64_t mid = mul32(s1, y0) + (uint64_t)__umulhi(s0, y0);
@@ -264,8 +277,8 @@ struct ArithS {
     {
         return tw(ld64(v, lane_off, slot_off), ld64(vs, lane_off, slot_off));
     }
-    // table entry i: per-lane index / wave-uniform index
-    static constexpr bool SCALAR_TW = false;
+    // table entry i: per-lane index / wave-uniform index (scalar registers, see mul<true>)
+    static constexpr bool SCALAR_TW = true;
     D2_DEV static Twid load_v(const Tw *table, uint32_t i)
     {
         const U128 e = ld128(table, 16u * i, 0);
@@ -277,9 +290,10 @@ struct ArithS {
     }
 
     // w*y mod q in [0, 4q), for y < 2^62.
+    template <bool SC = false>
     D2_DEV static elem mul(elem y, const Twid &w, const Mod &m)
     {
-        return shoup_tail(y, w.w, qhat_approx(y, w.ws), m.nq);
+        return shoup_tail<SC>(y, w.w, qhat_approx<SC>(y, w.ws), m.nq);
     }
     D2_DEV static elem from_small(int32_t v, const Mod &m)
     {
@@ -289,27 +303,30 @@ struct ArithS {
     D2_DEV static elem add(elem a, elem b) { return a + b; }
 
     // forward: no correction; each stage adds at most 4q to the bound
+    template <bool SC = false>
     D2_DEV static void ct(elem &x, elem &y, const Twid &w, const Mod &m)
     {
-        const elem t = mul(y, w, m);
+        const elem t = mul<SC>(y, w, m);
         const elem u = x;
         x = u + t;
         y = u + 4 * m.q - t;
     }
     D2_DEV static void fwd_pass_begin(elem &, const Mod &) {}
     // inverse: values in [0, 4q)
+    template <bool SC = false>
     D2_DEV static void gs(elem &x, elem &y, const Twid &w, const Mod &m)
     {
         const elem four_q = 4 * m.q;
         const elem s = x + y, d = x + four_q - y;
         x = csub(s, four_q);
-        y = mul(d, w, m);
+        y = mul<SC>(d, w, m);
     }
+    template <bool SC = false>
     D2_DEV static void gs_last(elem &x, elem &y, const Twid &ninv, const Twid &wn, const Mod &m)
     {
         const elem s = x + y, d = x + 4 * m.q - y;
-        x = mul(s, ninv, m);
-        y = mul(d, wn, m);
+        x = mul<SC>(s, ninv, m);
+        y = mul<SC>(d, wn, m);
     }
     D2_DEV static void inv_pass_begin(elem &, const Mod &) {}
     D2_DEV static elem inv_input(uint64_t canon, const Mod &) { return canon; }
@@ -346,8 +363,8 @@ struct ArithB {
     {
         return tw(ld64(v, lane_off, slot_off), ld64(vs, lane_off, slot_off));
     }
-    // table entry i: per-lane index / wave-uniform index
-    static constexpr bool SCALAR_TW = false;
+    // table entry i: per-lane index / wave-uniform index (scalar registers, see mul<true>)
+    static constexpr bool SCALAR_TW = true;
     D2_DEV static Twid load_v(const Tw *table, uint32_t i)
     {
         const U128 e = ld128(table, 16u * i, 0);
@@ -359,9 +376,10 @@ struct ArithB {
     }
 
     // w*y mod q in [0, 2q), for y < 2^63.
+    template <bool SC = false>
     D2_DEV static elem mul(elem y, const Twid &w, const Mod &m)
     {
-        return shoup_tail(y, w.w, qhat_exact(y, w.ws), m.nq);
+        return shoup_tail<SC>(y, w.w, qhat_exact<SC>(y, w.ws), m.nq);
     }
     D2_DEV static elem from_small(int32_t v, const Mod &m)
     {
@@ -371,28 +389,31 @@ struct ArithB {
     D2_DEV static elem add(elem a, elem b) { return a + b; }
 
     // x, y in [0, 4q) -> [0, 4q)
+    template <bool SC = false>
     D2_DEV static void ct(elem &x, elem &y, const Twid &w, const Mod &m)
     {
         const elem two_q = 2 * m.q;
         const elem u = csub(x, two_q);
-        const elem t = mul(y, w, m);
+        const elem t = mul<SC>(y, w, m);
         x = u + t;
         y = u + two_q - t;
     }
     D2_DEV static void fwd_pass_begin(elem &, const Mod &) {}
     // x, y in [0, 2q) -> [0, 2q)
+    template <bool SC = false>
     D2_DEV static void gs(elem &x, elem &y, const Twid &w, const Mod &m)
     {
         const elem two_q = 2 * m.q;
         const elem s = x + y, d = x + two_q - y;
         x = csub(s, two_q);
-        y = mul(d, w, m);
+        y = mul<SC>(d, w, m);
     }
+    template <bool SC = false>
     D2_DEV static void gs_last(elem &x, elem &y, const Twid &ninv, const Twid &wn, const Mod &m)
     {
         const elem s = x + y, d = x + 2 * m.q - y;
-        x = mul(s, ninv, m);
-        y = mul(d, wn, m);
+        x = mul<SC>(s, ninv, m);
+        y = mul<SC>(d, wn, m);
     }
     D2_DEV static void inv_pass_begin(elem &, const Mod &) {}
     D2_DEV static elem inv_input(uint64_t canon, const Mod &) { return canon; }
@@ -464,6 +485,7 @@ struct ArithF {
         return __builtin_fma(-b, m.q, x);
     }
     // w*y mod q as a signed representative of magnitude <= q/2 + 1, for |w y| < 2^96
+    template <bool SC = false>
     D2_DEV static elem mul(elem y, const Twid &w, const Mod &m)
     {
         const double h = w.w * y;
@@ -476,25 +498,28 @@ struct ArithF {
     D2_DEV static elem from_canon(uint64_t v, const Mod &) { return u2d(v); }
     D2_DEV static elem add(elem a, elem b) { return a + b; }
 
+    template <bool SC = false>
     D2_DEV static void ct(elem &x, elem &y, const Twid &w, const Mod &m)
     {
-        const elem t = mul(y, w, m);
+        const elem t = mul<SC>(y, w, m);
         const elem u = x;
         x = u + t;
         y = u - t;
     }
     D2_DEV static void fwd_pass_begin(elem &, const Mod &) {}
+    template <bool SC = false>
     D2_DEV static void gs(elem &x, elem &y, const Twid &w, const Mod &m)
     {
         const elem s = x + y, d = x - y;
         x = s;
-        y = mul(d, w, m);
+        y = mul<SC>(d, w, m);
     }
+    template <bool SC = false>
     D2_DEV static void gs_last(elem &x, elem &y, const Twid &ninv, const Twid &wn, const Mod &m)
     {
         const elem s = x + y, d = x - y;
-        x = mul(s, ninv, m);
-        y = mul(d, wn, m);
+        x = mul<SC>(s, ninv, m);
+        y = mul<SC>(d, wn, m);
     }
     // the sum path of the inverse doubles every stage: bring it back once per pass
     D2_DEV static void inv_pass_begin(elem &x, const Mod &m) { x = reduce(x, m); }

@@ -24,14 +24,19 @@ struct Launch {
                 const uint32_t n = polys_n - p0 < chunk_polys ? polys_n - p0 : chunk_polys;
                 uint64_t *base = polys + ((size_t)p0 << LOGN);
                 // limb of polynomial p = (p0 + p) % L: pass the offset so that the kernels see it
-                dim3 hgrid((1u << (LOGN - LOGH)) / 256, n), tgrid((1u << LOGH) * n);
+                // tail: TAIL_TILES tiles per workgroup; the grid is kept a multiple of 8 when the
+                // tile count is one, so that launch index and workgroup share their XCD
+                const uint32_t tiles = (1u << LOGH) * n;
+                uint32_t tgrid_x = (tiles + TAIL_TILES - 1) / TAIL_TILES;
+                if ((tiles & 7u) == 0) tgrid_x = (tgrid_x + 7u) & ~7u;
+                dim3 hgrid((1u << (LOGN - LOGH)) / 256, n), tgrid(tgrid_x);
                 if (forward) {
                     hipLaunchKernelGGL((k_head_forward<typename ENG::A, LOGN, LOGH>), hgrid, dim3(256), 0, st, base,
                                        ctx->d_tabs, L, p0);
                     D2_LAUNCHED(ctx);
-                    hipLaunchKernelGGL(k_tail_forward<ENG>, tgrid, dim3(ENG::T), 0, st, base, ctx->d_tabs, L, p0, n);
+                    hipLaunchKernelGGL(k_tail_forward<ENG>, tgrid, dim3(ENG::T), 0, st, base, ctx->d_tabs, L, p0, n, tiles);
                 } else {
-                    hipLaunchKernelGGL(k_tail_inverse<ENG>, tgrid, dim3(ENG::T), 0, st, base, ctx->d_tabs, L, p0, n);
+                    hipLaunchKernelGGL(k_tail_inverse<ENG>, tgrid, dim3(ENG::T), 0, st, base, ctx->d_tabs, L, p0, n, tiles);
                     D2_LAUNCHED(ctx);
                     hipLaunchKernelGGL((k_head_inverse<typename ENG::A, LOGN, LOGH>), hgrid, dim3(256), 0, st, base,
                                        ctx->d_tabs, L, p0);

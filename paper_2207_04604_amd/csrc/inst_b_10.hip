@@ -4,7 +4,7 @@
 namespace d2 {
 const EngineOps *ops_b_10()
 {
-    static const EngineOps ops = Launch<Engine<ArithB, 10, 4>>::full();
+    static const EngineOps ops = Launch<Engine<ArithB, 10, 3>>::full();
     return &ops;
 }
 }

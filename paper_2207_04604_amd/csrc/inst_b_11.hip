@@ -4,7 +4,7 @@
 namespace d2 {
 const EngineOps *ops_b_11()
 {
-    static const EngineOps ops = Launch<Engine<ArithB, 11, 4>>::full();
+    static const EngineOps ops = Launch<Engine<ArithB, 11, 3>>::full();
     return &ops;
 }
 }

@@ -4,7 +4,7 @@
 namespace d2 {
 const EngineOps *ops_f_10()
 {
-    static const EngineOps ops = Launch<Engine<ArithF, 10, 4>>::full();
+    static const EngineOps ops = Launch<Engine<ArithF, 10, 3>>::full();
     return &ops;
 }
 }

@@ -4,7 +4,7 @@
 namespace d2 {
 const EngineOps *ops_f_11()
 {
-    static const EngineOps ops = Launch<Engine<ArithF, 11, 4>>::full();
+    static const EngineOps ops = Launch<Engine<ArithF, 11, 3>>::full();
     return &ops;
 }
 }

@@ -163,7 +163,7 @@ __global__ void __launch_bounds__(256) k_head_forward(uint64_t *polys, const Lim
 #pragma unroll
             for (int j = 0; j < (1 << kb); ++j) {
                 const int k0 = (g << (kb + 1)) | j;
-                A::ct(x[k0], x[k0 | (1 << kb)], w, md);
+                A::template ct<A::SCALAR_TW>(x[k0], x[k0 | (1 << kb)], w, md);
             }
         }
     }
@@ -193,7 +193,7 @@ __global__ void __launch_bounds__(256) k_head_inverse(uint64_t *polys, const Lim
         const int s = LOGH - 1 - kb;
         if (kb == LOGH - 1) {                                    // last stage: fold N^-1
 #pragma unroll
-            for (int j = 0; j < (1 << kb); ++j) A::gs_last(x[j], x[j | (1 << kb)], A::tw(tb.ninv), A::tw(tb.wn), md);
+            for (int j = 0; j < (1 << kb); ++j) A::template gs_last<true>(x[j], x[j | (1 << kb)], A::tw(tb.ninv), A::tw(tb.wn), md);
         } else {
 #pragma unroll
             for (int g = 0; g < (H >> (kb + 1)); ++g) {
@@ -201,7 +201,7 @@ __global__ void __launch_bounds__(256) k_head_inverse(uint64_t *polys, const Lim
 #pragma unroll
                 for (int j = 0; j < (1 << kb); ++j) {
                     const int k0 = (g << (kb + 1)) | j;
-                    A::gs(x[k0], x[k0 | (1 << kb)], w, md);
+                    A::template gs<A::SCALAR_TW>(x[k0], x[k0 | (1 << kb)], w, md);
                 }
             }
         }
@@ -236,45 +236,86 @@ D2_DEV void tail_tile(uint32_t i, uint32_t total, uint32_t polys, uint32_t L, ui
     (void)poly0;
 }
 
-// tail: 1-D grid over (polynomial, block) tiles, see tail_tile
+// tail: every workgroup walks TAIL_TILES tiles, launch index v = blockIdx.x + i * gridDim.x (see
+// tail_tile for the tile of a launch index; with a grid that is a multiple of 8 a workgroup stays
+// on the twiddles of its XCD).  The coefficients of the next tile are requested before the current
+// one is transformed, so a wave always has a full tile of loads in flight behind its arithmetic.
+constexpr int TAIL_TILES = 4;
+
 template <class ENG>
 __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L,
-                                                        uint32_t poly0, uint32_t npolys)
+                                                        uint32_t poly0, uint32_t npolys, uint32_t total)
 {
     typedef typename ENG::A A;
+    constexpr int E = ENG::E;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
+    const uint32_t nblk = 1u << (ENG::LOGN - ENG::LOGB);
     uint32_t poly, blk;
-    tail_tile(blockIdx.x, gridDim.x, npolys, L, 1u << (ENG::LOGN - ENG::LOGB), poly0, poly, blk);
-    const LimbTab tb = load_tab(tabs, (poly0 + poly) % L);
-    const typename A::Mod md = A::mod(tb.q, tb.one_s);
-    uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
-    typename A::elem x[ENG::E];
+    uint64_t nx[E];
+    if (blockIdx.x >= total) return;
+    tail_tile(blockIdx.x, total, npolys, L, nblk, poly0, poly, blk);
+    {
+        const uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) x[k] = from_bits<A>(p[ENG::coef_pos(k, tid)]);
-    ENG::forward(x, lds, tid, blk, tb.fwd, md);
+        for (int k = 0; k < E; ++k) nx[k] = ld64(p, 8u * (uint32_t)tid, 8u * ENG::T * k);
+    }
+    for (uint32_t v = blockIdx.x; v < total; v += gridDim.x) {
+        const LimbTab tb = load_tab(tabs, (poly0 + poly) % L);
+        const typename A::Mod md = A::mod(tb.q, tb.one_s);
+        uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
+        const uint32_t cur_blk = blk;
+        typename A::elem x[E];
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) p[ENG::eval_pos(k, tid)] = A::canon_fwd(x[k], md);
+        for (int k = 0; k < E; ++k) x[k] = from_bits<A>(nx[k]);
+        if (v + gridDim.x < total) {
+            tail_tile(v + gridDim.x, total, npolys, L, nblk, poly0, poly, blk);
+            const uint64_t *pn = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
+#pragma unroll
+            for (int k = 0; k < E; ++k) nx[k] = ld64(pn, 8u * (uint32_t)tid, 8u * ENG::T * k);
+        }
+        ENG::forward(x, lds, tid, cur_blk, tb.fwd, md);
+#pragma unroll
+        for (int k = 0; k < E; ++k) st64(p, 8u * (uint32_t)tid, 8u * ENG::T * k, A::canon_fwd(x[k], md));
+    }
 }
 
 template <class ENG>
 __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L,
-                                                        uint32_t poly0, uint32_t npolys)
+                                                        uint32_t poly0, uint32_t npolys, uint32_t total)
 {
     typedef typename ENG::A A;
+    constexpr int E = ENG::E;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
+    const uint32_t nblk = 1u << (ENG::LOGN - ENG::LOGB);
     uint32_t poly, blk;
-    tail_tile(blockIdx.x, gridDim.x, npolys, L, 1u << (ENG::LOGN - ENG::LOGB), poly0, poly, blk);
-    const LimbTab tb = load_tab(tabs, (poly0 + poly) % L);
-    const typename A::Mod md = A::mod(tb.q, tb.one_s);
-    uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
-    typename A::elem x[ENG::E];
+    uint64_t nx[E];
+    if (blockIdx.x >= total) return;
+    tail_tile(blockIdx.x, total, npolys, L, nblk, poly0, poly, blk);
+    {
+        const uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) x[k] = A::inv_input(p[ENG::eval_pos(k, tid)], md);
-    ENG::template inverse<false>(x, lds, tid, blk, tb.inv, md, A::tw(tb.ninv), A::tw(tb.wn));
+        for (int k = 0; k < E; ++k) nx[k] = ld64(p, 8u * (uint32_t)tid, 8u * ENG::T * k);
+    }
+    for (uint32_t v = blockIdx.x; v < total; v += gridDim.x) {
+        const LimbTab tb = load_tab(tabs, (poly0 + poly) % L);
+        const typename A::Mod md = A::mod(tb.q, tb.one_s);
+        uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
+        const uint32_t cur_blk = blk;
+        typename A::elem x[E];
 #pragma unroll
-    for (int k = 0; k < ENG::E; ++k) p[ENG::coef_pos(k, tid)] = to_bits<A>(x[k]);   // lazy, head finishes
+        for (int k = 0; k < E; ++k) x[k] = A::inv_input(nx[k], md);
+        if (v + gridDim.x < total) {
+            tail_tile(v + gridDim.x, total, npolys, L, nblk, poly0, poly, blk);
+            const uint64_t *pn = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
+#pragma unroll
+            for (int k = 0; k < E; ++k) nx[k] = ld64(pn, 8u * (uint32_t)tid, 8u * ENG::T * k);
+        }
+        ENG::template inverse<false>(x, lds, tid, cur_blk, tb.inv, md, A::tw(tb.ninv), A::tw(tb.wn));
+#pragma unroll
+        for (int k = 0; k < E; ++k) st64(p, 8u * (uint32_t)tid, 8u * ENG::T * k, to_bits<A>(x[k]));   // lazy, head finishes
+    }
 }
 
 // -------------------------------------------------------------------------------------
@@ -610,26 +651,36 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
         const typename A::Mod md = A::mod(q, tb.one_s);
         const size_t off = (size_t)limb * ENG::NB;
         const int tl = opaque(tid);
-        // c0 + sum of the shares; the next member's values are in flight while this one's are added
+        // c0 + sum of the shares, one batch of loads per member; with 8 coefficients per thread the
+        // next member's values are already in flight while this one's are added
+        constexpr bool PIPE = E <= 8;
         uint64_t y[E], hv[E];
 #pragma unroll
         for (int k = 0; k < E; ++k) y[k] = ld64(c0 + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
-        if (K > 0) {
+        if (PIPE && K > 0) {
             const uint64_t *h = share_of(0) + (size_t)c * LN + off;
 #pragma unroll
             for (int k = 0; k < E; ++k) hv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
         }
         for (uint32_t j = 0; j < K; ++j) {
-            uint64_t nv[E];
-            if (j + 1 < K) {
-                const uint64_t *h = share_of(j + 1) + (size_t)c * LN + off;
+            if constexpr (PIPE) {
+                uint64_t nv[E];
+                if (j + 1 < K) {
+                    const uint64_t *h = share_of(j + 1) + (size_t)c * LN + off;
 #pragma unroll
-                for (int k = 0; k < E; ++k) nv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
-            }
+                    for (int k = 0; k < E; ++k) nv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
+                }
 #pragma unroll
-            for (int k = 0; k < E; ++k) {
-                y[k] = add_mod(y[k], hv[k], q);
-                hv[k] = nv[k];
+                for (int k = 0; k < E; ++k) {
+                    y[k] = add_mod(y[k], hv[k], q);
+                    hv[k] = nv[k];
+                }
+            } else {
+                const uint64_t *h = share_of(j) + (size_t)c * LN + off;
+#pragma unroll
+                for (int k = 0; k < E; ++k) hv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
+#pragma unroll
+                for (int k = 0; k < E; ++k) y[k] = add_mod(y[k], hv[k], q);
             }
         }
         typename A::elem x[E];

@@ -96,58 +96,90 @@ struct Engine {
     template <int P>
     static constexpr bool uniform_tw() { return A::SCALAR_TW && wbase(P) >= 6; }
 
-    // Fetch the twiddles of pass P (FOLD: the stage that multiplies by N^-1 takes none).  Issued
-    // one pass ahead of their use, so that the latency overlaps the butterflies and the exchange.
-    // DESC: requested in the order a forward pass uses them (highest stage bit first).
+    // A pass's twiddles are requested as one set, one pass ahead of their use (the latency then
+    // overlaps the butterflies and the exchange in between), if they sit in scalar registers or
+    // take at most 32 vector registers; otherwise stage by stage inside the pass.
+    template <int P>
+    static constexpr bool ahead() { return uniform_tw<P>() || (E - 1) * (int)(sizeof(Twid) / 4) <= 32; }
+
+    // The part of a twiddle index that depends on the thread.
+    template <int P>
+    D2_DEV static uint32_t tw_hi(int tid)
+    {
+        constexpr int wb = wbase(P);
+        // pass 0: T = 2^wb threads, nothing above the window.  Other uniform passes: taken from
+        // the hardware thread id, so that transforms sharing a table also share these loads.
+        if constexpr (wb == LOGB - ELOG) return 0;
+        else if constexpr (uniform_tw<P>()) return wave_uniform((uint32_t)threadIdx.x >> wb);
+        else return (uint32_t)(tid >> wb);
+    }
+
+    // Twiddles of the stage with block-index bit B_ of pass P -> DST[OFF_ .. OFF_ + (E >> (kb + 1)));
+    // written out where it is used: as a separate function the compiler no longer sees constant
+    // array indices and moves the arrays to scratch memory.
+#define D2_LOAD_STAGE(DST, OFF_, B_)                                                                        \
+    {                                                                                                      \
+        const int kb_ = (B_) - wbase(P);                   /* bit inside the register slot */              \
+        const int s_ = LOGN - 1 - (B_);                    /* stage number of the transform */             \
+        /* twiddle index = 2^s + (global index >> (b + 1)) */                                              \
+        const uint32_t base_ = (1u << s_) + (blk << (LOGB - (B_) - 1)) + (hi << (ELOG - kb_ - 1));         \
+        _Pragma("unroll") for (int g_ = 0; g_ < (E >> (kb_ + 1)); ++g_)                                    \
+        {                                                                                                  \
+            if constexpr (uniform_tw<P>()) DST[(OFF_) + g_] = A::load_u(tw, base_ + g_);                   \
+            else DST[(OFF_) + g_] = A::load_v(tw, base_ + g_);                                             \
+        }                                                                                                  \
+    }
+
+    // The whole set of pass P (nothing unless ahead<P>(); FOLD: the stage that multiplies by N^-1
+    // takes none).  DESC: in the order a forward pass uses them (highest stage bit first).
     template <int P, bool FOLD, bool DESC>
     D2_DEV static void load_tw(Twid (&w)[E], int tid, uint32_t blk, const Tw *tw)
     {
-        constexpr int wb = wbase(P), lo = sbit(P), r = stages(P);
-        uint32_t hi = (uint32_t)(tid >> wb);
-        // pass 0: T = 2^wb threads, nothing above the window.  Other uniform passes: taken from
-        // the hardware thread id, so that transforms sharing a table also share these loads.
-        if constexpr (wb == LOGB - ELOG) hi = 0;
-        else if constexpr (uniform_tw<P>()) hi = wave_uniform((uint32_t)threadIdx.x >> wb);
+        if constexpr (ahead<P>()) {
+            constexpr int wb = wbase(P), lo = sbit(P), r = stages(P);
+            const uint32_t hi = tw_hi<P>(tid);
 #pragma unroll
-        for (int i = 0; i < r; ++i) {
-            const int b = DESC ? lo + r - 1 - i : lo + i;  // stage bit inside the block index
-            const int kb = b - wb;                         // bit inside the register slot
-            const int s = LOGN - 1 - b;                    // stage number of the transform
-            if (FOLD && b == LOGN - 1) continue;
-            // twiddle index = 2^s + (global index >> (b + 1))
-            const uint32_t base = (1u << s) + (blk << (LOGB - b - 1)) + (hi << (ELOG - kb - 1));
-#pragma unroll
-            for (int g = 0; g < (E >> (kb + 1)); ++g) {
-                if constexpr (uniform_tw<P>()) w[tw_slot(kb, g)] = A::load_u(tw, base + g);
-                else w[tw_slot(kb, g)] = A::load_v(tw, base + g);
+            for (int i = 0; i < r; ++i) {
+                const int b = DESC ? lo + r - 1 - i : lo + i;
+                if (FOLD && b == LOGN - 1) continue;
+                D2_LOAD_STAGE(w, tw_slot(b - wb, 0), b)
             }
         }
     }
 
     template <int P>
-    D2_DEV static void fwd_pass(elem (&x)[E], const Twid (&w)[E], const Mod &md)
+    D2_DEV static void fwd_pass(elem (&x)[E], const Twid (&w)[E], int tid, uint32_t blk, const Tw *tw, const Mod &md)
     {
         constexpr int wb = wbase(P), lo = sbit(P), r = stages(P);
+        const uint32_t hi = tw_hi<P>(tid);
 #pragma unroll
         for (int b = lo + r - 1; b >= lo; --b) {           // stage bit inside the block index
             const int kb = b - wb;
+            Twid ws[E];
+            if constexpr (!ahead<P>()) D2_LOAD_STAGE(ws, 0, b)
 #pragma unroll
             for (int g = 0; g < (E >> (kb + 1)); ++g) {    // distinct twiddles of this stage
 #pragma unroll
                 for (int j = 0; j < (1 << kb); ++j) {
                     const int k0 = (g << (kb + 1)) | j;
-                    A::ct(x[k0], x[k0 | (1 << kb)], w[tw_slot(kb, g)], md);
+                    if constexpr (ahead<P>())
+                        A::template ct<uniform_tw<P>()>(x[k0], x[k0 | (1 << kb)], w[tw_slot(kb, g)], md);
+                    else
+                        A::template ct<uniform_tw<P>()>(x[k0], x[k0 | (1 << kb)], ws[g], md);
                 }
             }
         }
     }
 
     // FOLD: this pass contains the last stage of the whole inverse transform (bit LOGN-1)
-    // and multiplies by N^-1 there: ninv = N^-1, wn = (inverse twiddle 1) * N^-1.
+    // and multiplies by N^-1 there: ninv = N^-1, wn = (inverse twiddle 1) * N^-1, both uniform over
+    // the workgroup (they come from scalar loads of the per-modulus table).
     template <int P, bool FOLD>
-    D2_DEV static void inv_pass(elem (&x)[E], const Twid (&w)[E], const Mod &md, const Twid &ninv, const Twid &wn)
+    D2_DEV static void inv_pass(elem (&x)[E], const Twid (&w)[E], int tid, uint32_t blk, const Tw *tw, const Mod &md,
+                                const Twid &ninv, const Twid &wn)
     {
         constexpr int wb = wbase(P), lo = sbit(P), r = stages(P);
+        const uint32_t hi = tw_hi<P>(tid);
         if (P != NPASS - 1) {
 #pragma unroll
             for (int k = 0; k < E; ++k) A::inv_pass_begin(x[k], md);
@@ -157,14 +189,19 @@ struct Engine {
             const int kb = b - wb;
             if (FOLD && b == LOGN - 1) {
 #pragma unroll
-                for (int j = 0; j < (1 << kb); ++j) A::gs_last(x[j], x[j | (1 << kb)], ninv, wn, md);
+                for (int j = 0; j < (1 << kb); ++j) A::template gs_last<true>(x[j], x[j | (1 << kb)], ninv, wn, md);
             } else {
+                Twid ws[E];
+                if constexpr (!ahead<P>()) D2_LOAD_STAGE(ws, 0, b)
 #pragma unroll
                 for (int g = 0; g < (E >> (kb + 1)); ++g) {
 #pragma unroll
                     for (int j = 0; j < (1 << kb); ++j) {
                         const int k0 = (g << (kb + 1)) | j;
-                        A::gs(x[k0], x[k0 | (1 << kb)], w[tw_slot(kb, g)], md);
+                        if constexpr (ahead<P>())
+                            A::template gs<uniform_tw<P>()>(x[k0], x[k0 | (1 << kb)], w[tw_slot(kb, g)], md);
+                        else
+                            A::template gs<uniform_tw<P>()>(x[k0], x[k0 | (1 << kb)], ws[g], md);
                     }
                 }
             }
@@ -219,12 +256,12 @@ struct Engine {
     {
         if constexpr (P + 1 < NPASS) {
             Twid wn[E];
-            fwd_pass<P>(x, w, md);
+            fwd_pass<P>(x, w, tid, blk, tw, md);
             load_tw<P + 1, false, true>(wn, tid, blk, tw);
             exchange<P, P + 1>(x, lds, tid);
             fwd_from<P + 1>(x, wn, lds, tid, blk, tw, md);
         } else {
-            fwd_pass<P>(x, w, md);
+            fwd_pass<P>(x, w, tid, blk, tw, md);
         }
     }
 
@@ -234,12 +271,12 @@ struct Engine {
     {
         if constexpr (P > 0) {
             Twid wnext[E];
-            inv_pass<P, FOLD>(x, w, md, ninv, wn);
+            inv_pass<P, FOLD>(x, w, tid, blk, tw, md, ninv, wn);
             load_tw<P - 1, FOLD, false>(wnext, tid, blk, tw);
             exchange<P, P - 1>(x, lds, tid);
             inv_from<P - 1, FOLD>(x, wnext, lds, tid, blk, tw, md, ninv, wn);
         } else {
-            inv_pass<P, FOLD>(x, w, md, ninv, wn);
+            inv_pass<P, FOLD>(x, w, tid, blk, tw, md, ninv, wn);
         }
     }
 
