@@ -687,6 +687,94 @@ void orc_decrypt_with_secret(const orc_ctx *c, const uint64_t *s, const uint64_t
     free(y);
 }
 
+/* ---- MBFV.Convert (Sec. 4.2 item 3, Eq. (1)-(2)) ---- */
+
+/* BFV.SecKeyGen and BFV.PubKeyGen of one node (Sec. 3.2 items 1-2).                      */
+void orc_receiver_keygen(const orc_ctx *c, uint32_t party, uint64_t *sk, uint64_t *pk,
+                         int32_t *sk_small, int32_t *e_small)
+{
+    size_t n = c->n;
+    uint32_t L = c->p.num_limbs;
+    int32_t *s = (int32_t *)malloc(n * sizeof(int32_t));
+    int32_t *e = (int32_t *)malloc(n * sizeof(int32_t));
+    uint64_t *prod = (uint64_t *)malloc(n * sizeof(uint64_t));
+    orc_sample_ternary(c->p.seed, ORC_DOM_RSK, party, 0, 0, n, s);
+    orc_sample_cbd(c->p.seed, ORC_DOM_RPK_E, party, 0, 0, c->p.cbd_eta, n, e);
+    for (uint32_t i = 0; i < L; ++i) {
+        uint64_t q = c->p.q[i];
+        uint64_t *ski = sk + (size_t)i * n;
+        uint64_t *p0 = pk + (size_t)i * n;
+        uint64_t *p1 = pk + (size_t)(L + i) * n;
+        orc_sample_uniform(c->p.seed, ORC_DOM_RPK_A, i, party, 0, 0, q, n, p1);
+        for (size_t k = 0; k < n; ++k) ski[k] = lift_small(s[k], q);
+        orc_ring_mul(p1, ski, n, q, c->psi[i], prod);
+        for (size_t k = 0; k < n; ++k)
+            p0[k] = submod(0, addmod(prod[k], lift_small(e[k], q), q), q); /* -(p1 sk + e) */
+    }
+    if (sk_small) memcpy(sk_small, s, n * sizeof(int32_t));
+    if (e_small) memcpy(e_small, e, n * sizeof(int32_t));
+    free(s); free(e); free(prod);
+}
+
+void orc_convert_share(const orc_ctx *c, const uint64_t *sk_share, const uint64_t *pk_recv,
+                       const uint64_t *ct, uint32_t C, uint32_t party, uint32_t receiver,
+                       uint32_t group, uint32_t ct_base, uint64_t *share)
+{
+    size_t n = c->n;
+    uint32_t L = c->p.num_limbs;
+    uint32_t who = party | (receiver << 16);
+    int32_t *mu = (int32_t *)malloc(n * sizeof(int32_t));
+    int32_t *e0 = (int32_t *)malloc(n * sizeof(int32_t));
+    int32_t *e1 = (int32_t *)malloc(n * sizeof(int32_t));
+    uint64_t *mu_q = (uint64_t *)malloc(n * sizeof(uint64_t));
+    uint64_t *sc1 = (uint64_t *)malloc(n * sizeof(uint64_t));
+    uint64_t *prod = (uint64_t *)malloc(n * sizeof(uint64_t));
+    for (uint32_t ci = 0; ci < C; ++ci) {
+        uint32_t index = ct_base + ci;
+        orc_sample_ternary(c->p.seed, ORC_DOM_CVT_U, who, group, index, n, mu);
+        orc_sample_cbd(c->p.seed, ORC_DOM_CVT_E0, who, group, index, c->p.cbd_eta, n, e0);
+        orc_sample_cbd(c->p.seed, ORC_DOM_CVT_E1, who, group, index, c->p.cbd_eta, n, e1);
+        const uint64_t *c1 = ct + ((size_t)ci * 2 + 1) * L * n;
+        uint64_t *h0 = share + (size_t)ci * 2 * L * n;
+        uint64_t *h1 = h0 + (size_t)L * n;
+        for (uint32_t i = 0; i < L; ++i) {
+            uint64_t q = c->p.q[i];
+            const uint64_t *p0 = pk_recv + (size_t)i * n;
+            const uint64_t *p1 = pk_recv + (size_t)(L + i) * n;
+            for (size_t k = 0; k < n; ++k) mu_q[k] = lift_small(mu[k], q);
+            orc_ring_mul(sk_share + (size_t)i * n, c1 + (size_t)i * n, n, q, c->psi[i], sc1);
+            orc_ring_mul(mu_q, p0, n, q, c->psi[i], prod);
+            for (size_t k = 0; k < n; ++k)
+                h0[(size_t)i * n + k] = addmod(addmod(sc1[k], prod[k], q), lift_small(e0[k], q), q);
+            orc_ring_mul(mu_q, p1, n, q, c->psi[i], prod);
+            for (size_t k = 0; k < n; ++k)
+                h1[(size_t)i * n + k] = addmod(prod[k], lift_small(e1[k], q), q);
+        }
+    }
+    free(mu); free(e0); free(e1); free(mu_q); free(sc1); free(prod);
+}
+
+void orc_convert_combine(const orc_ctx *c, const uint64_t *ct, const uint64_t *const *shares,
+                         uint32_t K, uint32_t C, uint64_t *ct_out)
+{
+    size_t n = c->n;
+    uint32_t L = c->p.num_limbs;
+    for (uint32_t ci = 0; ci < C; ++ci)
+        for (uint32_t i = 0; i < L; ++i) {
+            uint64_t q = c->p.q[i];
+            size_t o0 = ((size_t)ci * 2 * L + i) * n, o1 = o0 + (size_t)L * n;
+            for (size_t k = 0; k < n; ++k) {
+                uint64_t a0 = ct[o0 + k], a1 = 0; /* the old c1 is dropped */
+                for (uint32_t m = 0; m < K; ++m) {
+                    a0 = addmod(a0, shares[m][o0 + k], q);
+                    a1 = addmod(a1, shares[m][o1 + k], q);
+                }
+                ct_out[o0 + k] = a0;
+                ct_out[o1 + k] = a1;
+            }
+        }
+}
+
 void orc_bench_polys(const orc_ctx *c, uint32_t B, uint64_t *out)
 {
     for (uint32_t b = 0; b < B; ++b)

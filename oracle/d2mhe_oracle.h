@@ -38,7 +38,14 @@ enum {
     ORC_DOM_ENC_E0 = 0x05, /* error e0 of Encrypt                      */
     ORC_DOM_ENC_E1 = 0x06, /* error e1 of Encrypt                      */
     ORC_DOM_DEC_E = 0x07,  /* smudging error of a decryption share     */
-    ORC_DOM_BENCH = 0x08   /* uniform benchmark polynomials (per limb) */
+    ORC_DOM_BENCH = 0x08,  /* uniform benchmark polynomials (per limb) */
+    /* MBFV.Convert (Sec. 4.2 item 3) */
+    ORC_DOM_RSK = 0x10,    /* ternary single-key secret of a receiver  */
+    ORC_DOM_RPK_A = 0x11,  /* uniform p1 of a receiver's public key (per limb) */
+    ORC_DOM_RPK_E = 0x12,  /* error of a receiver's public key         */
+    ORC_DOM_CVT_U = 0x13,  /* mu_k of a conversion share               */
+    ORC_DOM_CVT_E0 = 0x14, /* e0_k of a conversion share               */
+    ORC_DOM_CVT_E1 = 0x15  /* e1_k of a conversion share               */
 };
 
 typedef struct {
@@ -123,9 +130,28 @@ void orc_combine(const orc_ctx *c, const uint64_t *ct, const uint64_t *const *sh
 /* plaintext polynomials -> slots -> centred -> float.                                   */
 int orc_decode(const orc_ctx *c, const uint64_t *pt, uint32_t C, uint64_t n_values,
                float *out);
-/* Single-key BFV.Decrypt with an explicit secret s [L][N] (used only by the pins).      */
+/* Single-key BFV.Decrypt with an explicit secret s [L][N]: the receiver's last step after
+ * MBFV.Convert, and a cross-check of the collective decryption in the pins.             */
 void orc_decrypt_with_secret(const orc_ctx *c, const uint64_t *s, const uint64_t *ct,
                              uint32_t C, uint64_t *pt);
+
+/* ---- MBFV.Convert: key switching to a receiver's own key (Sec. 4.2 item 3) ---- */
+/* Receiver i's single-key BFV pair (Sec. 3.2 items 1-2): sk_i ternary, p1_i uniform in R_q,
+ * p0_i = -(p1_i sk_i + e).  sk [L][N], pk [2][L][N] = (p0_i, p1_i); counter party word = i.
+ * sk_small/e_small (nullable) receive the signed coefficients [N].                      */
+void orc_receiver_keygen(const orc_ctx *c, uint32_t party, uint64_t *sk, uint64_t *pk,
+                         int32_t *sk_small, int32_t *e_small);
+/* Member k's share towards receiver i, Eq. (1):
+ *   (h0, h1) = (s_k c1 + mu_k p0_i + e0_k, mu_k p1_i + e1_k),   share [C][2][L][N].
+ * mu_k is ternary (the same distribution as in Encrypt), e0_k, e1_k from chi; their counter
+ * party word is k | i << 16, group and ciphertext index as in Encrypt.                   */
+void orc_convert_share(const orc_ctx *c, const uint64_t *sk_share, const uint64_t *pk_recv,
+                       const uint64_t *ct, uint32_t C, uint32_t party, uint32_t receiver,
+                       uint32_t group, uint32_t ct_base, uint64_t *share);
+/* The receiver's new ciphertext E' = (c0 + sum_k h0_k, sum_k h1_k), ct_out [C][2][L][N];
+ * BFV.Decrypt(sk_i, E') is orc_decrypt_with_secret (Eq. (2)).                            */
+void orc_convert_combine(const orc_ctx *c, const uint64_t *ct, const uint64_t *const *shares,
+                         uint32_t K, uint32_t C, uint64_t *ct_out);
 
 /* Uniform benchmark polynomials: out [B][L][N], polynomial b of the batch, limb i.      */
 void orc_bench_polys(const orc_ctx *c, uint32_t B, uint64_t *out);

@@ -80,6 +80,9 @@ def lib():
             "orc_combine": (None, [vp, vp, vp, u32, u32, vp]),
             "orc_decode": (i32, [vp, vp, u32, u64, vp]),
             "orc_decrypt_with_secret": (None, [vp, vp, vp, u32, vp]),
+            "orc_receiver_keygen": (None, [vp, u32, vp, vp, vp, vp]),
+            "orc_convert_share": (None, [vp, vp, vp, vp, u32, u32, u32, u32, u32, vp]),
+            "orc_convert_combine": (None, [vp, vp, vp, u32, u32, vp]),
             "orc_bench_polys": (None, [vp, u32, vp]),
             "orc_ntt_forward_batch": (None, [vp, vp, u32]),
             "orc_ntt_inverse_batch": (None, [vp, vp, u32]),
@@ -293,6 +296,30 @@ class Oracle:
         pt = np.zeros((ct.shape[0], self.N), dtype=np.uint64)
         lib().orc_decrypt_with_secret(self._h, _p(s), _p(ct), ct.shape[0], _p(pt))
         return pt
+
+    # ---- MBFV.Convert (Sec. 4.2 item 3) ----
+    def receiver_keygen(self, party):
+        sk = np.zeros((self.L, self.N), dtype=np.uint64)
+        pk = np.zeros((2, self.L, self.N), dtype=np.uint64)
+        s_small = np.zeros(self.N, dtype=np.int32)
+        e_small = np.zeros(self.N, dtype=np.int32)
+        lib().orc_receiver_keygen(self._h, party, _p(sk), _p(pk), _p(s_small), _p(e_small))
+        return sk, pk, s_small, e_small
+
+    def convert_share(self, sk_share, pk_recv, ct, party, receiver, group, ct_base=0):
+        sk_share, pk_recv, ct = _u64(sk_share), _u64(pk_recv), _u64(ct)
+        C_ = ct.shape[0]
+        share = np.zeros((C_, 2, self.L, self.N), dtype=np.uint64)
+        lib().orc_convert_share(self._h, _p(sk_share), _p(pk_recv), _p(ct), C_, party, receiver, group,
+                                ct_base, _p(share))
+        return share
+
+    def convert_combine(self, ct, shares):
+        ct = _u64(ct)
+        shares = [_u64(s) for s in shares]
+        out = np.zeros_like(ct)
+        lib().orc_convert_combine(self._h, _p(ct), _ptr_array(shares), len(shares), ct.shape[0], _p(out))
+        return out
 
     def bench_polys(self, B):
         out = np.zeros((B, self.L, self.N), dtype=np.uint64)

@@ -79,7 +79,8 @@ def crt(residues, qs):
 class PyBFV:
     """Multiparty BFV over Z_Q (Q = prod q_i), straight from Sec. 3.2 and Sec. 4.2."""
 
-    DOM = dict(SK=1, PK_E=2, CRS=3, ENC_U=4, ENC_E0=5, ENC_E1=6, DEC_E=7)
+    DOM = dict(SK=1, PK_E=2, CRS=3, ENC_U=4, ENC_E0=5, ENC_E1=6, DEC_E=7,
+               RSK=0x10, RPK_A=0x11, RPK_E=0x12, CVT_U=0x13, CVT_E0=0x14, CVT_E1=0x15)
 
     def __init__(self, n, qs, t, eta, frac_bits, max_group, seed, psi_t):
         self.n, self.qs, self.t, self.eta = n, list(qs), t, eta
@@ -172,3 +173,34 @@ class PyBFV:
             v = (ct[0][k] + sc1[k] - self.Lam * m[k]) % self.Q
             out.append(v - self.Q if v > self.Q // 2 else v)
         return out
+
+    # ---- MBFV.Convert (Sec. 4.2 item 3): key switching to the receiver's own key ----
+    def receiver_keygen(self, party):
+        """Single-key BFV pair of one node (Sec. 3.2 items 1-2), over Z_Q."""
+        s = ternary(self.seed, self.DOM["RSK"], party, 0, 0, self.n)
+        e = cbd(self.seed, self.DOM["RPK_E"], party, 0, 0, self.eta, self.n)
+        limbs = [uniform(self.seed, self.DOM["RPK_A"], i, party, 0, 0, q, self.n)
+                 for i, q in enumerate(self.qs)]
+        p1 = [crt([limbs[i][k] for i in range(len(self.qs))], self.qs) for k in range(self.n)]
+        sp = negacyclic(p1, s, self.Q)
+        p0 = [(-(sp[k] + e[k])) % self.Q for k in range(self.n)]
+        return s, e, (p0, p1)
+
+    def convert_share(self, s_k, pk_i, ct, party, receiver, group, cti):
+        """Eq. (1): (h0, h1) = (s_k c1 + mu_k p0_i + e0_k, mu_k p1_i + e1_k)."""
+        who = party | (receiver << 16)
+        mu = ternary(self.seed, self.DOM["CVT_U"], who, group, cti, self.n)
+        e0 = cbd(self.seed, self.DOM["CVT_E0"], who, group, cti, self.eta, self.n)
+        e1 = cbd(self.seed, self.DOM["CVT_E1"], who, group, cti, self.eta, self.n)
+        sc1 = negacyclic(ct[1], s_k, self.Q)
+        mp0 = negacyclic(pk_i[0], mu, self.Q)
+        mp1 = negacyclic(pk_i[1], mu, self.Q)
+        h0 = [(sc1[k] + mp0[k] + e0[k]) % self.Q for k in range(self.n)]
+        h1 = [(mp1[k] + e1[k]) % self.Q for k in range(self.n)]
+        return (h0, h1), (mu, e0, e1)
+
+    def convert_combine(self, ct, shares):
+        """E' = (c0 + sum h0_k, sum h1_k)."""
+        c0 = [(ct[0][k] + sum(h[0][k] for h in shares)) % self.Q for k in range(self.n)]
+        c1 = [sum(h[1][k] for h in shares) % self.Q for k in range(self.n)]
+        return c0, c1

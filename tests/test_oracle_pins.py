@@ -312,6 +312,86 @@ def test_whole_round_equals_bruteforce_big_integer_bfv(orc, log2n, bits, L, t, K
     assert [float(v) for v in out] == [v / (1 << f) for v in expect_sum]
 
 
+@pytest.mark.parametrize("log2n,bits,L,t,K,recv", [(3, 30, 2, 17, 3, 1), (4, 36, 3, 97, 4, 0), (4, 60, 4, 65537, 2, 7),
+                                                  (3, 30, 1, 17, 1, 0)])
+def test_convert_equals_bruteforce_big_integer_bfv(orc, log2n, bits, L, t, K, recv):
+    """MBFV.Convert (Sec. 4.2 item 3): receiver key, every share (Eq. (1)), the converted ciphertext
+    and its single-key decryption (Eq. (2)) against the big-integer reference; `recv` = 7 is a
+    receiver outside the group (the formulas do not need it to be a member)."""
+    f = 3
+    o, ref, qs = _toy(orc, log2n, bits, L, t, K, f)
+    n = 1 << log2n
+    rng = np.random.default_rng(log2n * 1000 + L)
+    group, cti = 3, 9
+    keys = [ref.keygen(k) for k in range(K)]
+    p0 = ref.aggregate_pk([k[2] for k in keys])
+    okeys = [o.keygen_share(k) for k in range(K)]
+    opk = o.aggregate_pk([k[1] for k in okeys])
+    # the receiver's own pair
+    rs, re_, rpk = ref.receiver_keygen(recv)
+    osk, orpk, os_small, oe_small = o.receiver_keygen(recv)
+    assert list(os_small) == rs and list(oe_small) == re_
+    assert np.array_equal(osk, _residues(rs, qs))
+    assert np.array_equal(orpk[0], _residues(rpk[0], qs)) and np.array_equal(orpk[1], _residues(rpk[1], qs))
+    # p0_i + p1_i sk_i = -e  (Sec. 3.2 item 2)
+    lhs = [(a + b) % ref.Q for a, b in zip(rpk[0], pyref.negacyclic(rpk[1], rs, ref.Q))]
+    assert lhs == [(-v) % ref.Q for v in re_]
+    # aggregate of K fresh ciphertexts
+    ms = [[int(v) for v in rng.integers(0, t, n)] for _ in range(K)]
+    cts = [ref.encrypt(p0, ms[k], k, group, cti)[0] for k in range(K)]
+    octs = [o.encrypt(opk, np.array([ms[k]], dtype=np.uint64), k, group, ct_base=cti) for k in range(K)]
+    agg, oagg = cts[0], octs[0]
+    for k in range(1, K):
+        agg = ref.add(agg, cts[k])
+        oagg = o.add(oagg, octs[k])
+    # shares towards the receiver
+    shares = [ref.convert_share(keys[k][0], rpk, agg, k, recv, group, cti)[0] for k in range(K)]
+    oshares = [o.convert_share(okeys[k][0], orpk, oagg, k, recv, group, ct_base=cti) for k in range(K)]
+    for k in range(K):
+        assert np.array_equal(oshares[k][0, 0], _residues(shares[k][0], qs))
+        assert np.array_equal(oshares[k][0, 1], _residues(shares[k][1], qs))
+    new_ct = ref.convert_combine(agg, shares)
+    onew = o.convert_combine(oagg, oshares)
+    assert np.array_equal(onew[0, 0], _residues(new_ct[0], qs)) and np.array_equal(onew[0, 1], _residues(new_ct[1], qs))
+    # the receiver alone decrypts the sum (Eq. (2)); the collective decryption gives the same
+    expect = [sum(m[j] for m in ms) % t for j in range(n)]
+    assert ref.decrypt(rs, new_ct) == expect
+    assert [int(v) for v in o.decrypt_with_secret(osk, onew)[0]] == expect
+    plain_shares = [o.partial_decrypt(okeys[k][0], oagg, k, group, ct_base=cti) for k in range(K)]
+    assert [int(v) for v in o.combine(oagg, plain_shares)[0]] == expect
+    # a share towards another receiver uses other randomness
+    other = o.convert_share(okeys[0][0], orpk, oagg, 0, recv + 1, group, ct_base=cti)
+    assert not np.array_equal(other, oshares[0])
+
+
+def test_convert_noise_identity(orc):
+    """Eq. (2) expanded: c0' + sk_i c1' - Lambda m = e_ct + e0 + sk_i e1 - mu e_cl exactly, with
+    e_ct the noise of the input ciphertext, e_d = sum e_{d,k}, mu = sum mu_k and e_cl the error of
+    the receiver's public key (p0_i = -(sk_i p1_i + e_cl)); and it stays below Q/(2t)."""
+    o, ref, qs = _toy(orc, 5, 36, 2, 193, 3, 2)
+    n, K, recv, group, cti = 32, 3, 2, 1, 4
+    keys = [ref.keygen(k) for k in range(K)]
+    p0 = ref.aggregate_pk([k[2] for k in keys])
+    s = [sum(k[0][j] for k in keys) for j in range(n)]
+    rs, e_cl, rpk = ref.receiver_keygen(recv)
+    m = [(11 * j + 3) % 193 for j in range(n)]
+    ct = ref.encrypt(p0, m, 1, group, cti)[0]
+    e_ct = ref.noise(s, ct, m)
+    parts = [ref.convert_share(keys[k][0], rpk, ct, k, recv, group, cti) for k in range(K)]
+    new_ct = ref.convert_combine(ct, [p[0] for p in parts])
+    mu = [sum(p[1][0][j] for p in parts) for j in range(n)]
+    e0 = [sum(p[1][1][j] for p in parts) for j in range(n)]
+    e1 = [sum(p[1][2][j] for p in parts) for j in range(n)]
+    centred = lambda poly: [v - ref.Q if v > ref.Q // 2 else v for v in poly]
+    lift = lambda poly: [v % ref.Q for v in poly]
+    sk_e1 = centred(pyref.negacyclic(lift(rs), lift(e1), ref.Q))
+    mu_ecl = centred(pyref.negacyclic(lift(mu), lift(e_cl), ref.Q))
+    noise = ref.noise(rs, new_ct, m)
+    assert noise == [e_ct[k] + e0[k] + sk_e1[k] - mu_ecl[k] for k in range(n)]
+    assert max(abs(v) for v in noise) < ref.Q // (2 * 193)
+    assert ref.decrypt(rs, new_ct) == m
+
+
 def test_noise_identity_and_margin(orc):
     """c0 + c1 s - Lambda m = -mu e_pk + e0 + e1 s exactly (Sec. 3.2 item 3 expanded), and it
     stays below Q/(2t) minus the wrap term (correctness condition under Eq. (2))."""
