@@ -175,6 +175,56 @@ d2mhe_status d2mhe_round_group(d2mhe_ctx *ctx, const uint64_t *pk,
                                uint64_t n_values, float *out_sum, void *scratch,
                                size_t scratch_bytes, void *stream);
 
+/* ---- MBFV.Convert: key switching to a receiver's own key (Sec. 4.2 item 3) ------------------- */
+/* In the paper's protocol node i does not take part in a collective decryption of the
+ * aggregate; the members of its closed neighbourhood switch the aggregate to node i's own
+ * public key pk_i, and node i decrypts alone (Eq. (1), (2)).
+ *
+ * A node's own single-key pair (BFV.SecKeyGen / BFV.PubKeyGen, Sec. 3.2 items 1-2):
+ * sk ternary, p1 uniform in R_q, p0 = -(p1 sk + e).  sk: prepared polynomial (2*L*N words);
+ * pk: two prepared polynomials (p0, p1), 4*L*N words.  Randomness indexed by the party id. */
+d2mhe_status d2mhe_receiver_keygen(d2mhe_ctx *ctx, uint32_t party, uint64_t *sk, uint64_t *pk,
+                                   void *stream);
+/* Member `party`'s share towards `receiver`, Eq. (1):
+ *   (h0, h1) = (s_k c1 + mu_k p0_i + e0_k, mu_k p1_i + e1_k),   share [C][2][L][N],
+ * mu_k ternary (the distribution of mu in BFV.Encrypt), e0_k, e1_k from chi; randomness indexed
+ * by (party | receiver << 16, group, ct_base + c).  pk_recv: the receiver's prepared key.  */
+d2mhe_status d2mhe_convert_share(d2mhe_ctx *ctx, const uint64_t *sk_share, const uint64_t *pk_recv,
+                                 const uint64_t *ct, uint32_t C, uint32_t party, uint32_t receiver,
+                                 uint32_t group, uint32_t ct_base, uint64_t *share, void *stream);
+/* The converted ciphertext E' = (c0 + sum_k h0_k, sum_k h1_k), ct_out [C][2][L][N] (may not
+ * alias ct).  shares: HOST array of K device pointers.                                      */
+d2mhe_status d2mhe_convert_combine(d2mhe_ctx *ctx, const uint64_t *ct, const uint64_t *const *shares,
+                                   uint32_t K, uint32_t C, uint64_t *ct_out, void *stream);
+/* BFV.Decrypt with a single prepared secret key (Sec. 3.2 item 5): pt = [round(t (c0 + c1 sk) / Q)]_t,
+ * pt [C][N]; rounding as in d2mhe_combine.                                                  */
+d2mhe_status d2mhe_decrypt(d2mhe_ctx *ctx, const uint64_t *sk, const uint64_t *ct, uint32_t C,
+                           uint64_t *pt, void *stream);
+
+/* Receivers of a fused round: group g is converted to each of
+ * receivers[recv_offsets[g] .. recv_offsets[g+1]) (party ids; at least one per group).  HOST
+ * arrays of device pointers, as in d2mhe_round_desc.                                        */
+typedef struct {
+    const uint32_t *recv_offsets;    /* [G+1], recv_offsets[0] = 0, strictly increasing      */
+    const uint32_t *receivers;       /* [recv_offsets[G]] party ids                          */
+    const uint64_t *const *recv_pks; /* [P] prepared single-key public key by party id       */
+    const uint64_t *const *recv_sks; /* [P] prepared single-key secret key by party id       */
+    float *const *out_recv;          /* [recv_offsets[G]] result per (group, receiver)       */
+} d2mhe_convert_desc;
+
+/* Scratch bytes of d2mhe_round_convert; num_shares = sum over groups of members * receivers. */
+size_t d2mhe_round_convert_scratch_bytes(const d2mhe_ctx *ctx, uint32_t num_jobs, uint32_t num_groups,
+                                         uint32_t num_shares, uint64_t n_values);
+/* d2mhe_round with the paper's decryption path: after the sum, every member of group g makes
+ * one conversion share per receiver of g, and every receiver combines its shares with the
+ * aggregate and decrypts with its own key into out_recv (desc->out_sums is not used).  The
+ * scratch then holds the fresh ciphertexts [J][C][2][L][N], the aggregates [G][C][2][L][N] and
+ * the conversion shares [num_shares][C][2][L][N], ordered by (group, receiver, member).
+ * phase_events as in d2mhe_round.                                                           */
+d2mhe_status d2mhe_round_convert(d2mhe_ctx *ctx, const d2mhe_round_desc *desc,
+                                 const d2mhe_convert_desc *conv, void *scratch, size_t scratch_bytes,
+                                 void *const *phase_events, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

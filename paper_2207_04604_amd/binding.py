@@ -22,6 +22,8 @@ SYMBOLS = [
     "d2mhe_keygen_share", "d2mhe_aggregate_pk", "d2mhe_encode", "d2mhe_encrypt", "d2mhe_add",
     "d2mhe_partial_decrypt", "d2mhe_combine", "d2mhe_decode", "d2mhe_round_scratch_bytes",
     "d2mhe_round", "d2mhe_round_group",
+    "d2mhe_receiver_keygen", "d2mhe_convert_share", "d2mhe_convert_combine", "d2mhe_decrypt",
+    "d2mhe_round_convert_scratch_bytes", "d2mhe_round_convert",
 ]
 
 
@@ -37,6 +39,12 @@ class RoundDesc(C.Structure):
                 ("pks", C.POINTER(C.c_void_p)), ("num_parties", C.c_uint32),
                 ("sk_shares", C.POINTER(C.c_void_p)), ("grads", C.POINTER(C.c_void_p)),
                 ("out_sums", C.POINTER(C.c_void_p)), ("n_values", C.c_uint64)]
+
+
+class ConvertDesc(C.Structure):
+    _fields_ = [("recv_offsets", C.POINTER(C.c_uint32)), ("receivers", C.POINTER(C.c_uint32)),
+                ("recv_pks", C.POINTER(C.c_void_p)), ("recv_sks", C.POINTER(C.c_void_p)),
+                ("out_recv", C.POINTER(C.c_void_p))]
 
 
 class D2mheError(RuntimeError):
@@ -80,6 +88,12 @@ def lib():
         "d2mhe_round_scratch_bytes": (sz, [vp, u32, u32, u64]),
         "d2mhe_round": (i32, [vp, C.POINTER(RoundDesc), vp, sz, vp, vp]),
         "d2mhe_round_group": (i32, [vp, vp, vp, vp, vp, u32, u32, u64, vp, vp, sz, vp]),
+        "d2mhe_receiver_keygen": (i32, [vp, u32, vp, vp, vp]),
+        "d2mhe_convert_share": (i32, [vp, vp, vp, vp, u32, u32, u32, u32, u32, vp, vp]),
+        "d2mhe_convert_combine": (i32, [vp, vp, vp, u32, u32, vp, vp]),
+        "d2mhe_decrypt": (i32, [vp, vp, vp, u32, vp, vp]),
+        "d2mhe_round_convert_scratch_bytes": (sz, [vp, u32, u32, u32, u64]),
+        "d2mhe_round_convert": (i32, [vp, C.POINTER(RoundDesc), C.POINTER(ConvertDesc), vp, sz, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -236,6 +250,52 @@ class Context:
     def round(self, desc, scratch, scratch_bytes, phase_events=None, stream=None):
         ev = (C.c_void_p * 5)(*phase_events) if phase_events is not None else None
         _check(lib().d2mhe_round(self._h, C.byref(desc), _ptr(scratch), scratch_bytes, ev, stream), "d2mhe_round")
+
+    # ---- MBFV.Convert ----
+    def receiver_keygen(self, party, sk, pk, stream=None):
+        _check(lib().d2mhe_receiver_keygen(self._h, party, _ptr(sk), _ptr(pk), stream), "d2mhe_receiver_keygen")
+
+    def convert_share(self, sk_share, pk_recv, ct, C_, party, receiver, group, ct_base, share, stream=None):
+        _check(lib().d2mhe_convert_share(self._h, _ptr(sk_share), _ptr(pk_recv), _ptr(ct), C_, party, receiver,
+                                         group, ct_base, _ptr(share), stream), "d2mhe_convert_share")
+
+    def convert_combine(self, ct, shares, C_, ct_out, stream=None):
+        _check(lib().d2mhe_convert_combine(self._h, _ptr(ct), _ptr_table(shares), len(shares), C_, _ptr(ct_out),
+                                           stream), "d2mhe_convert_combine")
+
+    def decrypt(self, sk, ct, C_, pt, stream=None):
+        _check(lib().d2mhe_decrypt(self._h, _ptr(sk), _ptr(ct), C_, _ptr(pt), stream), "d2mhe_decrypt")
+
+    def round_convert_scratch_bytes(self, num_jobs, num_groups, num_shares, n_values):
+        return lib().d2mhe_round_convert_scratch_bytes(self._h, num_jobs, num_groups, num_shares, n_values)
+
+    def make_convert(self, desc, receivers, recv_pks, recv_sks, out_recv):
+        """Receivers of a round made by make_round(): receivers = one list of party ids per group;
+        recv_pks / recv_sks by party id (list or dict); out_recv: one buffer per (group, receiver)."""
+        flat = [int(r) for g in receivers for r in g]
+        offs = [0]
+        for g in receivers:
+            offs.append(offs[-1] + len(g))
+        P = desc.num_parties
+        get = (lambda tbl, k: tbl.get(k)) if isinstance(recv_pks, dict) else (lambda tbl, k: tbl[k] if k < len(tbl) else None)
+        keep = {
+            "offs": (C.c_uint32 * len(offs))(*offs),
+            "recv": (C.c_uint32 * len(flat))(*flat),
+            "pks": (C.c_void_p * P)(*[_ptr(get(recv_pks, k)) for k in range(P)]),
+            "sks": (C.c_void_p * P)(*[_ptr(get(recv_sks, k)) for k in range(P)]),
+            "outs": _ptr_table(out_recv),
+        }
+        cd = ConvertDesc(keep["offs"], keep["recv"], C.cast(keep["pks"], C.POINTER(C.c_void_p)),
+                         C.cast(keep["sks"], C.POINTER(C.c_void_p)), C.cast(keep["outs"], C.POINTER(C.c_void_p)))
+        cd._keep = keep
+        groups = [desc._keep["offs"][g + 1] - desc._keep["offs"][g] for g in range(desc.num_groups)]
+        cd.num_shares = sum(k * len(r) for k, r in zip(groups, receivers))
+        return cd
+
+    def round_convert(self, desc, conv, scratch, scratch_bytes, phase_events=None, stream=None):
+        ev = (C.c_void_p * 5)(*phase_events) if phase_events is not None else None
+        _check(lib().d2mhe_round_convert(self._h, C.byref(desc), C.byref(conv), _ptr(scratch), scratch_bytes, ev,
+                                         stream), "d2mhe_round_convert")
 
     def round_group(self, pk, sk_shares, grads, members, group, n_values, out_sum, scratch, scratch_bytes,
                     stream=None):

@@ -53,6 +53,15 @@ struct EngineOps {
                             uint64_t *pt, hipStream_t);
     d2mhe_status (*combine_decode)(d2mhe_ctx *, const GroupJobs &jobs, uint32_t njobs, size_t stride, uint32_t C,
                                    uint64_t n_values, hipStream_t);
+    // MBFV.Convert
+    d2mhe_status (*receiver_keygen)(d2mhe_ctx *, uint32_t party, uint64_t *sk, uint64_t *pk, hipStream_t);
+    d2mhe_status (*convert_share)(d2mhe_ctx *, const ConvJobs &jobs, uint32_t njobs, uint32_t ct_base, uint32_t C,
+                                  hipStream_t);
+    // y = c0 + sum h0_k + (c1 if keep_c1 + sum h1_k) sk, rounded: plaintext polynomials
+    d2mhe_status (*convert_combine)(d2mhe_ctx *, const uint64_t *ct, const PtrList &shares, uint32_t K,
+                                    const uint64_t *sk, bool keep_c1, uint32_t C, uint64_t *pt, hipStream_t);
+    d2mhe_status (*convert_combine_decode)(d2mhe_ctx *, const RecvJobs &jobs, uint32_t njobs, size_t stride,
+                                           uint32_t C, uint64_t n_values, hipStream_t);
 };
 
 const EngineOps *ops_f_10();

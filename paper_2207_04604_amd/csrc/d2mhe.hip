@@ -500,30 +500,90 @@ d2mhe_status d2mhe_combine(d2mhe_ctx *ctx, const uint64_t *ct, const uint64_t *c
     return engine_ops(ctx)->combine(ctx, ct, sh, K, C, pt, (hipStream_t)stream);
 }
 
-namespace {
+// ---- MBFV.Convert ------------------------------------------------------------------------------
 
-// words of scratch for J (party, group) jobs, G groups, C ciphertext indices
-size_t round_words(const d2mhe_ctx *ctx, uint64_t J, uint64_t G, uint64_t C)
-{
-    const size_t LN = (size_t)ctx->L * ctx->N;
-    return (size_t)C * ((size_t)J * 2 * LN + (size_t)G * 2 * LN + (size_t)J * LN);
-}
-
-}  // namespace
-
-size_t d2mhe_round_scratch_bytes(const d2mhe_ctx *ctx, uint32_t num_jobs, uint32_t num_groups, uint64_t n_values)
-{
-    if (!ctx || !ctx->t || num_jobs == 0 || num_groups == 0) return 0;
-    const uint64_t C = (n_values + ctx->N - 1) / ctx->N;
-    return round_words(ctx, num_jobs, num_groups, C) * sizeof(uint64_t);
-}
-
-d2mhe_status d2mhe_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, void *scratch, size_t scratch_bytes,
-                         void *const *phase_events, void *stream)
+d2mhe_status d2mhe_receiver_keygen(d2mhe_ctx *ctx, uint32_t party, uint64_t *sk, uint64_t *pk, void *stream)
 {
     D2_NEED_SCHEME(ctx);
+    if (!sk || !pk) return D2MHE_ERR_NULL;
+    if (misaligned(sk) || misaligned(pk)) return D2MHE_ERR_ALIGN;
+    if (party > 0xffffu) return D2MHE_ERR_RANGE;
+    return engine_ops(ctx)->receiver_keygen(ctx, party, sk, pk, (hipStream_t)stream);
+}
+
+d2mhe_status d2mhe_convert_share(d2mhe_ctx *ctx, const uint64_t *sk_share, const uint64_t *pk_recv,
+                                 const uint64_t *ct, uint32_t C, uint32_t party, uint32_t receiver, uint32_t group,
+                                 uint32_t ct_base, uint64_t *share, void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!sk_share || !pk_recv || !ct || !share) return D2MHE_ERR_NULL;
+    if (misaligned(sk_share) || misaligned(pk_recv) || misaligned(ct) || misaligned(share)) return D2MHE_ERR_ALIGN;
+    if (party > 0xffffu || receiver > 0xffffu || group > 0xffffu || (uint64_t)ct_base + C > 0xffffffffull)
+        return D2MHE_ERR_RANGE;
+    if (C == 0) return D2MHE_OK;
+    ConvJobs jobs;
+    jobs.sk[0] = sk_share;
+    jobs.pk[0] = pk_recv;
+    jobs.ct[0] = ct;
+    jobs.out[0] = share;
+    jobs.who[0] = party | (receiver << 16);
+    jobs.group[0] = group;
+    return engine_ops(ctx)->convert_share(ctx, jobs, 1, ct_base, C, (hipStream_t)stream);
+}
+
+d2mhe_status d2mhe_convert_combine(d2mhe_ctx *ctx, const uint64_t *ct, const uint64_t *const *shares, uint32_t K,
+                                   uint32_t C, uint64_t *ct_out, void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!ct || !shares || !ct_out) return D2MHE_ERR_NULL;
+    if (K == 0 || K > (uint32_t)MAX_GROUP || K > ctx->max_group) return D2MHE_ERR_RANGE;
+    if (misaligned(ct) || misaligned(ct_out)) return D2MHE_ERR_ALIGN;
+    PtrList sh;
+    for (uint32_t k = 0; k < K; ++k) {
+        if (!shares[k]) return D2MHE_ERR_NULL;
+        if (misaligned(shares[k])) return D2MHE_ERR_ALIGN;
+        sh.p[k] = shares[k];
+    }
+    if (C == 0) return D2MHE_OK;
+    const size_t LN = (size_t)ctx->L * ctx->N, total = (size_t)C * 2 * LN;
+    hipLaunchKernelGGL(k_convert_sum, dim3((unsigned)((total / 2 + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       ct_out, ct, sh, K, ctx->d_tabs, ctx->L, ctx->log2n, LN, total);
+    D2_LAUNCHED(ctx);
+    return D2MHE_OK;
+}
+
+d2mhe_status d2mhe_decrypt(d2mhe_ctx *ctx, const uint64_t *sk, const uint64_t *ct, uint32_t C, uint64_t *pt,
+                           void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!sk || !ct || !pt) return D2MHE_ERR_NULL;
+    if (misaligned(sk) || misaligned(ct) || misaligned(pt)) return D2MHE_ERR_ALIGN;
+    if (C == 0) return D2MHE_OK;
+    PtrList none;
+    none.p[0] = nullptr;
+    return engine_ops(ctx)->convert_combine(ctx, ct, none, 0, sk, true, C, pt, (hipStream_t)stream);
+}
+
+namespace {
+
+// words of scratch for J (party, group) jobs, G groups, C ciphertext indices; S conversion shares
+// (0: collective decryption, one single-polynomial share per job)
+size_t round_words(const d2mhe_ctx *ctx, uint64_t J, uint64_t G, uint64_t S, uint64_t C)
+{
+    const size_t LN = (size_t)ctx->L * ctx->N;
+    const size_t shares = S ? (size_t)S * 2 * LN : (size_t)J * LN;
+    return (size_t)C * ((size_t)J * 2 * LN + (size_t)G * 2 * LN + shares);
+}
+
+// One exchange round; conv == nullptr: collective decryption of every aggregate, otherwise key
+// switching to every receiver (MBFV.Convert) and single-key decryption.
+d2mhe_status run_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_convert_desc *conv, void *scratch,
+                       size_t scratch_bytes, void *const *phase_events, void *stream)
+{
     if (!d || !scratch) return D2MHE_ERR_NULL;
-    if (!d->group_offsets || !d->members || !d->pks || !d->sk_shares || !d->grads || !d->out_sums)
+    if (!d->group_offsets || !d->members || !d->pks || !d->sk_shares || !d->grads) return D2MHE_ERR_NULL;
+    if (!conv && !d->out_sums) return D2MHE_ERR_NULL;
+    if (conv && (!conv->recv_offsets || !conv->receivers || !conv->recv_pks || !conv->recv_sks || !conv->out_recv))
         return D2MHE_ERR_NULL;
     const uint32_t G = d->num_groups;
     if (G == 0 || G > 0xffffu) return D2MHE_ERR_RANGE;
@@ -533,8 +593,12 @@ d2mhe_status d2mhe_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, void *scratc
         if (d->group_offsets[g + 1] <= d->group_offsets[g]) return D2MHE_ERR_RANGE;
         const uint32_t K = d->group_offsets[g + 1] - d->group_offsets[g];
         if (K > (uint32_t)MAX_GROUP || K > ctx->max_group) return D2MHE_ERR_RANGE;
-        if (!d->pks[g] || !d->out_sums[g]) return D2MHE_ERR_NULL;
-        if (misaligned(d->pks[g]) || misaligned(d->out_sums[g])) return D2MHE_ERR_ALIGN;
+        if (!d->pks[g]) return D2MHE_ERR_NULL;
+        if (misaligned(d->pks[g])) return D2MHE_ERR_ALIGN;
+        if (!conv) {
+            if (!d->out_sums[g]) return D2MHE_ERR_NULL;
+            if (misaligned(d->out_sums[g])) return D2MHE_ERR_ALIGN;
+        }
     }
     for (uint32_t j = 0; j < J; ++j) {
         const uint32_t party = d->members[j];
@@ -542,12 +606,31 @@ d2mhe_status d2mhe_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, void *scratc
         if (!d->sk_shares[party] || !d->grads[party]) return D2MHE_ERR_NULL;
         if (misaligned(d->sk_shares[party]) || misaligned(d->grads[party])) return D2MHE_ERR_ALIGN;
     }
+    uint64_t S = 0;          // conversion shares
+    uint32_t R = 0;          // (group, receiver) pairs
+    if (conv) {
+        if (conv->recv_offsets[0] != 0) return D2MHE_ERR_RANGE;
+        for (uint32_t g = 0; g < G; ++g) {
+            if (conv->recv_offsets[g + 1] <= conv->recv_offsets[g]) return D2MHE_ERR_RANGE;
+            S += (uint64_t)(conv->recv_offsets[g + 1] - conv->recv_offsets[g]) *
+                 (d->group_offsets[g + 1] - d->group_offsets[g]);
+        }
+        R = conv->recv_offsets[G];
+        if (S > 0xffffffffull) return D2MHE_ERR_RANGE;
+        for (uint32_t r = 0; r < R; ++r) {
+            const uint32_t party = conv->receivers[r];
+            if (party >= d->num_parties || party > 0xffffu) return D2MHE_ERR_RANGE;
+            if (!conv->recv_pks[party] || !conv->recv_sks[party] || !conv->out_recv[r]) return D2MHE_ERR_NULL;
+            if (misaligned(conv->recv_pks[party]) || misaligned(conv->recv_sks[party]) || misaligned(conv->out_recv[r]))
+                return D2MHE_ERR_ALIGN;
+        }
+    }
     if (misaligned(scratch)) return D2MHE_ERR_ALIGN;
     if (d->n_values == 0) return D2MHE_OK;
     const uint64_t C64 = (d->n_values + ctx->N - 1) / ctx->N;
     if (C64 > 0x7fffffffull) return D2MHE_ERR_RANGE;
     const uint32_t C = (uint32_t)C64;
-    if (scratch_bytes < round_words(ctx, J, G, C) * sizeof(uint64_t)) return D2MHE_ERR_WORKSPACE;
+    if (scratch_bytes < round_words(ctx, J, G, S, C) * sizeof(uint64_t)) return D2MHE_ERR_WORKSPACE;
 
     const size_t LN = (size_t)ctx->L * ctx->N;
     const size_t ct_words = (size_t)C * 2 * LN, sh_words = (size_t)C * LN;
@@ -596,39 +679,123 @@ d2mhe_status d2mhe_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, void *scratc
     }
     if (ev) D2_HIP(ctx, hipEventRecord(ev[2], st));
 
-    // phase 3: every member's decryption share of its group's aggregate
-    for (uint32_t j0 = 0; j0 < J; j0 += JOB_CHUNK) {
-        const uint32_t n = J - j0 < (uint32_t)JOB_CHUNK ? J - j0 : (uint32_t)JOB_CHUNK;
-        ShareJobs jobs;
-        for (uint32_t i = 0; i < n; ++i) {
-            const uint32_t j = j0 + i, g = group_of[j];
-            jobs.sk[i] = d->sk_shares[d->members[j]];
-            jobs.ct[i] = agg + (size_t)g * ct_words;
-            jobs.out[i] = shares + (size_t)j * sh_words;
-            jobs.party[i] = d->members[j];
-            jobs.group[i] = d->group_ids ? d->group_ids[g] : g;
+    if (!conv) {
+        // phase 3: every member's decryption share of its group's aggregate
+        for (uint32_t j0 = 0; j0 < J; j0 += JOB_CHUNK) {
+            const uint32_t n = J - j0 < (uint32_t)JOB_CHUNK ? J - j0 : (uint32_t)JOB_CHUNK;
+            ShareJobs jobs;
+            for (uint32_t i = 0; i < n; ++i) {
+                const uint32_t j = j0 + i, g = group_of[j];
+                jobs.sk[i] = d->sk_shares[d->members[j]];
+                jobs.ct[i] = agg + (size_t)g * ct_words;
+                jobs.out[i] = shares + (size_t)j * sh_words;
+                jobs.party[i] = d->members[j];
+                jobs.group[i] = d->group_ids ? d->group_ids[g] : g;
+            }
+            d2mhe_status s = ops->share(ctx, jobs, n, 0, C, st);
+            if (s != D2MHE_OK) return s;
         }
-        d2mhe_status s = ops->share(ctx, jobs, n, 0, C, st);
+        if (ev) D2_HIP(ctx, hipEventRecord(ev[3], st));
+
+        // phase 4: combine the shares, round, decode
+        for (uint32_t g0 = 0; g0 < G; g0 += JOB_CHUNK) {
+            const uint32_t n = G - g0 < (uint32_t)JOB_CHUNK ? G - g0 : (uint32_t)JOB_CHUNK;
+            GroupJobs jobs;
+            for (uint32_t i = 0; i < n; ++i) {
+                const uint32_t g = g0 + i;
+                jobs.first[i] = shares + (size_t)d->group_offsets[g] * sh_words;
+                jobs.ct[i] = agg + (size_t)g * ct_words;
+                jobs.out[i] = d->out_sums[g];
+                jobs.K[i] = d->group_offsets[g + 1] - d->group_offsets[g];
+            }
+            d2mhe_status s = ops->combine_decode(ctx, jobs, n, sh_words, C, d->n_values, st);
+            if (s != D2MHE_OK) return s;
+        }
+        if (ev) D2_HIP(ctx, hipEventRecord(ev[4], st));
+        return D2MHE_OK;
+    }
+
+    // phase 3 (Convert): one share per (group, receiver, member), in that order
+    struct ShareRef {
+        uint32_t g, r, j;      // group, index into receivers, index into members
+    };
+    std::vector<ShareRef> refs;
+    refs.reserve((size_t)S);
+    std::vector<size_t> first_share(R);     // position of the first share of a (group, receiver) pair
+    for (uint32_t g = 0; g < G; ++g)
+        for (uint32_t r = conv->recv_offsets[g]; r < conv->recv_offsets[g + 1]; ++r) {
+            first_share[r] = refs.size();
+            for (uint32_t j = d->group_offsets[g]; j < d->group_offsets[g + 1]; ++j) refs.push_back(ShareRef{g, r, j});
+        }
+    for (size_t s0 = 0; s0 < refs.size(); s0 += CONV_CHUNK) {
+        const uint32_t n = (uint32_t)(refs.size() - s0 < (size_t)CONV_CHUNK ? refs.size() - s0 : (size_t)CONV_CHUNK);
+        ConvJobs jobs;
+        for (uint32_t i = 0; i < n; ++i) {
+            const ShareRef &f = refs[s0 + i];
+            const uint32_t member = d->members[f.j], receiver = conv->receivers[f.r];
+            jobs.sk[i] = d->sk_shares[member];
+            jobs.pk[i] = conv->recv_pks[receiver];
+            jobs.ct[i] = agg + (size_t)f.g * ct_words;
+            jobs.out[i] = shares + (s0 + i) * ct_words;
+            jobs.who[i] = member | (receiver << 16);
+            jobs.group[i] = d->group_ids ? d->group_ids[f.g] : f.g;
+        }
+        d2mhe_status s = ops->convert_share(ctx, jobs, n, 0, C, st);
         if (s != D2MHE_OK) return s;
     }
     if (ev) D2_HIP(ctx, hipEventRecord(ev[3], st));
 
-    // phase 4: combine the shares, round, decode
-    for (uint32_t g0 = 0; g0 < G; g0 += JOB_CHUNK) {
-        const uint32_t n = G - g0 < (uint32_t)JOB_CHUNK ? G - g0 : (uint32_t)JOB_CHUNK;
-        GroupJobs jobs;
+    // phase 4 (Convert): every receiver forms its ciphertext, decrypts with its own key, decodes
+    for (uint32_t r0 = 0; r0 < R; r0 += CONV_CHUNK) {
+        const uint32_t n = R - r0 < (uint32_t)CONV_CHUNK ? R - r0 : (uint32_t)CONV_CHUNK;
+        RecvJobs jobs;
+        uint32_t g = 0;
         for (uint32_t i = 0; i < n; ++i) {
-            const uint32_t g = g0 + i;
-            jobs.first[i] = shares + (size_t)d->group_offsets[g] * sh_words;
+            const uint32_t r = r0 + i;
+            while (conv->recv_offsets[g + 1] <= r) ++g;
+            jobs.first[i] = shares + first_share[r] * ct_words;
             jobs.ct[i] = agg + (size_t)g * ct_words;
-            jobs.out[i] = d->out_sums[g];
+            jobs.sk[i] = conv->recv_sks[conv->receivers[r]];
+            jobs.out[i] = conv->out_recv[r];
             jobs.K[i] = d->group_offsets[g + 1] - d->group_offsets[g];
         }
-        d2mhe_status s = ops->combine_decode(ctx, jobs, n, sh_words, C, d->n_values, st);
+        d2mhe_status s = ops->convert_combine_decode(ctx, jobs, n, ct_words, C, d->n_values, st);
         if (s != D2MHE_OK) return s;
     }
     if (ev) D2_HIP(ctx, hipEventRecord(ev[4], st));
     return D2MHE_OK;
+}
+
+}  // namespace
+
+size_t d2mhe_round_scratch_bytes(const d2mhe_ctx *ctx, uint32_t num_jobs, uint32_t num_groups, uint64_t n_values)
+{
+    if (!ctx || !ctx->t || num_jobs == 0 || num_groups == 0) return 0;
+    const uint64_t C = (n_values + ctx->N - 1) / ctx->N;
+    return round_words(ctx, num_jobs, num_groups, 0, C) * sizeof(uint64_t);
+}
+
+size_t d2mhe_round_convert_scratch_bytes(const d2mhe_ctx *ctx, uint32_t num_jobs, uint32_t num_groups,
+                                         uint32_t num_shares, uint64_t n_values)
+{
+    if (!ctx || !ctx->t || num_jobs == 0 || num_groups == 0 || num_shares == 0) return 0;
+    const uint64_t C = (n_values + ctx->N - 1) / ctx->N;
+    return round_words(ctx, num_jobs, num_groups, num_shares, C) * sizeof(uint64_t);
+}
+
+d2mhe_status d2mhe_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, void *scratch, size_t scratch_bytes,
+                         void *const *phase_events, void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    return run_round(ctx, d, nullptr, scratch, scratch_bytes, phase_events, stream);
+}
+
+d2mhe_status d2mhe_round_convert(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_convert_desc *conv,
+                                 void *scratch, size_t scratch_bytes, void *const *phase_events, void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!conv) return D2MHE_ERR_NULL;
+    return run_round(ctx, d, conv, scratch, scratch_bytes, phase_events, stream);
 }
 
 d2mhe_status d2mhe_round_group(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_t *const *sk_shares,

@@ -109,16 +109,53 @@ struct Launch {
         return D2MHE_OK;
     }
 
+    static d2mhe_status receiver_keygen(d2mhe_ctx *ctx, uint32_t party, uint64_t *sk, uint64_t *pk, hipStream_t st)
+    {
+        hipLaunchKernelGGL(k_receiver_keygen<ENG>, dim3(ctx->L), dim3(ENG::T), 0, st, party, sk, pk, ctx->d_tabs,
+                           ctx->rc);
+        D2_LAUNCHED(ctx);
+        return D2MHE_OK;
+    }
+
+    static d2mhe_status convert_share(d2mhe_ctx *ctx, const ConvJobs &jobs, uint32_t njobs, uint32_t ct_base,
+                                      uint32_t C, hipStream_t st)
+    {
+        hipLaunchKernelGGL(k_convert_share<ENG>, dim3(C, njobs), dim3(ENG::T), 0, st, jobs, ct_base, ctx->d_tabs,
+                           ctx->rc);
+        D2_LAUNCHED(ctx);
+        return D2MHE_OK;
+    }
+
+    static d2mhe_status convert_combine(d2mhe_ctx *ctx, const uint64_t *ct, const PtrList &shares, uint32_t K,
+                                        const uint64_t *sk, bool keep_c1, uint32_t C, uint64_t *pt, hipStream_t st)
+    {
+        hipLaunchKernelGGL(k_convert_combine<ENG>, dim3(C), dim3(ENG::T), 0, st, ct, shares, K, sk, keep_c1 ? 1 : 0,
+                           pt, ctx->d_tabs, ctx->rc);
+        D2_LAUNCHED(ctx);
+        return D2MHE_OK;
+    }
+
+    static d2mhe_status convert_combine_decode(d2mhe_ctx *ctx, const RecvJobs &jobs, uint32_t njobs, size_t stride,
+                                               uint32_t C, uint64_t n_values, hipStream_t st)
+    {
+        hipLaunchKernelGGL(k_convert_combine_decode<ENG>, dim3(C, njobs), dim3(ENG::T), 0, st, jobs, stride,
+                           n_values, ctx->d_tabs, ctx->rc);
+        D2_LAUNCHED(ctx);
+        return D2MHE_OK;
+    }
+
     // full set (ring degrees a single workgroup can hold)
     static EngineOps full()
     {
         return EngineOps{ENG::ELOG, ENG::LOGB, &ntt, &keygen, &encode, &decode, &encrypt, &share, &combine,
-                         &combine_decode};
+                         &combine_decode, &receiver_keygen, &convert_share, &convert_combine,
+                         &convert_combine_decode};
     }
     // transforms only (longer rings)
     static EngineOps transforms_only()
     {
-        return EngineOps{ENG::ELOG, ENG::LOGB, &ntt, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+        return EngineOps{ENG::ELOG, ENG::LOGB, &ntt,    nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                         nullptr,   nullptr,   nullptr, nullptr, nullptr};
     }
 };
 

@@ -76,11 +76,27 @@ struct ShareJobs {                     // one job = one member's shares of C agg
     uint32_t party[JOB_CHUNK];
     uint32_t group[JOB_CHUNK];
 };
+constexpr int CONV_CHUNK = 80;         // 80 * 40 B of table
+struct ConvJobs {                      // one job = one member's conversion shares towards one receiver
+    const uint64_t *sk[CONV_CHUNK];    // the member's prepared secret share
+    const uint64_t *pk[CONV_CHUNK];    // the receiver's prepared public key
+    const uint64_t *ct[CONV_CHUNK];    // aggregate [C][2][L][N]
+    uint64_t *out[CONV_CHUNK];         // shares [C][2][L][N]
+    uint32_t who[CONV_CHUNK];          // member | receiver << 16: the party word of the counters
+    uint32_t group[CONV_CHUNK];
+};
 struct GroupJobs {                     // one job = one group: K buffers laid out at a fixed stride
     const uint64_t *first[JOB_CHUNK];  // buffer of the group's first member
     const uint64_t *ct[JOB_CHUNK];     // aggregate (combine) / unused (sum)
     void *out[JOB_CHUNK];              // aggregate (sum) / decoded floats (combine)
     uint32_t K[JOB_CHUNK];
+};
+struct RecvJobs {                      // one job = one receiver of one group (MBFV.Convert)
+    const uint64_t *first[CONV_CHUNK]; // conversion shares of the group's first member for this receiver
+    const uint64_t *ct[CONV_CHUNK];    // aggregate
+    const uint64_t *sk[CONV_CHUNK];    // the receiver's prepared secret key
+    void *out[CONV_CHUNK];             // decoded floats
+    uint32_t K[CONV_CHUNK];
 };
 
 D2_DEV uint32_t bitrev(uint32_t v, int bits) { return __brev(v) >> (32 - bits); }
@@ -322,18 +338,19 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_inverse(uint64_t *p
 // Sampling helpers: small polynomials are drawn block by block, staged in LDS as packed
 // words (one per coefficient, natural order) and then picked up by their pass-0 owners.
 // -------------------------------------------------------------------------------------
-// mu (ternary) in byte 0, e0 in byte 1, e1 in byte 2 (two's complement bytes)
+// mu (ternary) in byte 0, e0 in byte 1, e1 in byte 2 (two's complement bytes); their domains are
+// dom, dom + 1, dom + 2 (DOM_ENC_U for Encrypt, DOM_CVT_U for a conversion share)
 template <class ENG>
-D2_DEV void stage_encrypt_samples(uint32_t *lds32, int tid, uint32_t party, uint32_t group, uint32_t ct,
-                                  const RoundConst &rc)
+D2_DEV void stage_encrypt_samples(uint32_t *lds32, int tid, uint32_t dom, uint32_t party, uint32_t group,
+                                  uint32_t ct, const RoundConst &rc)
 {
     for (int j = tid; j < ENG::NB / 4; j += ENG::T) {
         int32_t mu[4], e0[4], e1[4];
-        ternary4(philox4x32_10(j, ct, party, counter_tag(DOM_ENC_U, 0, group), rc.key), mu);
-        cbd2(philox4x32_10(2 * j, ct, party, counter_tag(DOM_ENC_E0, 0, group), rc.key), rc.eta_mask, e0);
-        cbd2(philox4x32_10(2 * j + 1, ct, party, counter_tag(DOM_ENC_E0, 0, group), rc.key), rc.eta_mask, e0 + 2);
-        cbd2(philox4x32_10(2 * j, ct, party, counter_tag(DOM_ENC_E1, 0, group), rc.key), rc.eta_mask, e1);
-        cbd2(philox4x32_10(2 * j + 1, ct, party, counter_tag(DOM_ENC_E1, 0, group), rc.key), rc.eta_mask, e1 + 2);
+        ternary4(philox4x32_10(j, ct, party, counter_tag(dom, 0, group), rc.key), mu);
+        cbd2(philox4x32_10(2 * j, ct, party, counter_tag(dom + 1, 0, group), rc.key), rc.eta_mask, e0);
+        cbd2(philox4x32_10(2 * j + 1, ct, party, counter_tag(dom + 1, 0, group), rc.key), rc.eta_mask, e0 + 2);
+        cbd2(philox4x32_10(2 * j, ct, party, counter_tag(dom + 2, 0, group), rc.key), rc.eta_mask, e1);
+        cbd2(philox4x32_10(2 * j + 1, ct, party, counter_tag(dom + 2, 0, group), rc.key), rc.eta_mask, e1 + 2);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             lds32[4 * j + i] = ((uint32_t)mu[i] & 0xffu) | (((uint32_t)e0[i] & 0xffu) << 8) |
@@ -521,7 +538,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
     }
     uint32_t smp[E];
     __syncthreads();
-    stage_encrypt_samples<ENG>(lds32, tid, party, group, ct_base + c, rc);
+    stage_encrypt_samples<ENG>(lds32, tid, DOM_ENC_U, party, group, ct_base + c, rc);
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < E; ++k) smp[k] = lds32[ENG::coef_pos(k, tid)];
@@ -630,17 +647,23 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_share(ShareJobs jobs, ui
 // by summing t * y_i' / q_i over the limbs with y_i' = y_i (Q/q_i)^-1 mod q_i: integer
 // parts exactly, fractional parts in 64-bit fixed point (each term is truncated by less
 // than 2^-63, so the rounding is exact unless t y / Q lies within L * 2^-63 of a half-integer).
-// SH(j) returns the share buffer [C][L][N] of member j.
+// SH(j) returns the share buffer of member j.
+// CONVERT (MBFV.Convert, Eq. (2)): a share is a pair (h0, h1) [C][2][L][N] and the receiver's
+// single-key decryption is folded in: y = c0 + sum h0_k + (z0 + sum h1_k) sk, where z0 = c1 of
+// `ct` if keep_c1 (plain BFV.Decrypt of `ct` when K = 0) and 0 otherwise (the converted
+// ciphertext drops the old c1).  skr: the receiver's prepared secret key.
 // -------------------------------------------------------------------------------------
-template <class ENG, bool DECODE, class SH>
-D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_t K, uint64_t *pt, float *out,
-                         uint64_t n_values, const LimbTab *tabs, const RoundConst &rc)
+template <class ENG, bool DECODE, bool CONVERT, class SH>
+D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_t K, const uint64_t *skr,
+                         bool keep_c1, uint64_t *pt, float *out, uint64_t n_values, const LimbTab *tabs,
+                         const RoundConst &rc)
 {
     typedef typename ENG::A A;
     constexpr int E = ENG::E;
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x, L = rc.L;
     const size_t LN = (size_t)L * ENG::NB;
+    const size_t share_ct = (CONVERT ? 2 : 1) * LN;       // words of one share per ciphertext index
     const uint64_t *c0 = ct + (size_t)c * 2 * LN;
     uint64_t acc_int[E], acc_frac[E];
 #pragma unroll
@@ -653,12 +676,12 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
         const int tl = opaque(tid);
         // c0 + sum of the shares, one batch of loads per member; with 8 coefficients per thread the
         // next member's values are already in flight while this one's are added
-        constexpr bool PIPE = E <= 8;
+        constexpr bool PIPE = E <= 8 && !CONVERT;
         uint64_t y[E], hv[E];
 #pragma unroll
         for (int k = 0; k < E; ++k) y[k] = ld64(c0 + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
         if (PIPE && K > 0) {
-            const uint64_t *h = share_of(0) + (size_t)c * LN + off;
+            const uint64_t *h = share_of(0) + (size_t)c * share_ct + off;
 #pragma unroll
             for (int k = 0; k < E; ++k) hv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
         }
@@ -666,7 +689,7 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
             if constexpr (PIPE) {
                 uint64_t nv[E];
                 if (j + 1 < K) {
-                    const uint64_t *h = share_of(j + 1) + (size_t)c * LN + off;
+                    const uint64_t *h = share_of(j + 1) + (size_t)c * share_ct + off;
 #pragma unroll
                     for (int k = 0; k < E; ++k) nv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
                 }
@@ -676,7 +699,7 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
                     hv[k] = nv[k];
                 }
             } else {
-                const uint64_t *h = share_of(j) + (size_t)c * LN + off;
+                const uint64_t *h = share_of(j) + (size_t)c * share_ct + off;
 #pragma unroll
                 for (int k = 0; k < E; ++k) hv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
 #pragma unroll
@@ -684,8 +707,29 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
             }
         }
         typename A::elem x[E];
+        if constexpr (CONVERT) {
+            uint64_t z[E];
 #pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = A::inv_input(y[k], md);
+            for (int k = 0; k < E; ++k) z[k] = keep_c1 ? ld64(c0 + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k) : 0;
+            for (uint32_t j = 0; j < K; ++j) {
+                const uint64_t *h = share_of(j) + (size_t)c * share_ct + LN + off;
+#pragma unroll
+                for (int k = 0; k < E; ++k) hv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
+#pragma unroll
+                for (int k = 0; k < E; ++k) z[k] = add_mod(z[k], hv[k], q);
+            }
+            typename A::Twid kv[E];
+#pragma unroll
+            for (int k = 0; k < E; ++k) kv[k] = A::key(skr + off, skr + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
+#pragma unroll
+            for (int k = 0; k < E; ++k) {
+                const typename A::elem prod = A::mul(A::from_canon(z[k], md), kv[k], md);
+                x[k] = A::inv_input(A::canon_acc(A::add(prod, A::from_canon(y[k], md)), md), md);
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < E; ++k) x[k] = A::inv_input(y[k], md);
+        }
         ENG::template inverse<true>(x, lds, tl, 0, tb.inv, md, A::tw(tb.ninv), A::tw(tb.wn));
 #pragma unroll
         for (int k = 0; k < E; ++k) {
@@ -727,8 +771,8 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_combine(const uint64_t *
                                                     const LimbTab *tabs, RoundConst rc)
 {
     __shared__ uint64_t lds[ENG::LDS_WORDS];
-    combine_body<ENG, false>(lds, ct, [&](uint32_t j) { return (const uint64_t *)shares.p[j]; }, K, pt,
-                             (float *)nullptr, 0, tabs, rc);
+    combine_body<ENG, false, false>(lds, ct, [&](uint32_t j) { return (const uint64_t *)shares.p[j]; }, K,
+                                    (const uint64_t *)nullptr, false, pt, (float *)nullptr, 0, tabs, rc);
 }
 
 // whole round: grid = (C, groups); the group's shares lie `stride` words apart; decoded floats out
@@ -739,8 +783,188 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_combine_decode(GroupJobs
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const uint32_t job = blockIdx.y;
     const uint64_t *first = jobs.first[job];
-    combine_body<ENG, true>(lds, jobs.ct[job], [&](uint32_t j) { return first + (size_t)j * stride; }, jobs.K[job],
-                            (uint64_t *)nullptr, (float *)jobs.out[job], n_values, tabs, rc);
+    combine_body<ENG, true, false>(lds, jobs.ct[job], [&](uint32_t j) { return first + (size_t)j * stride; },
+                                   jobs.K[job], (const uint64_t *)nullptr, false, (uint64_t *)nullptr,
+                                   (float *)jobs.out[job], n_values, tabs, rc);
+}
+
+// -------------------------------------------------------------------------------------
+// MBFV.Convert (Sec. 4.2 item 3): key switching of an aggregate to a receiver's own key.
+// -------------------------------------------------------------------------------------
+// Set-up: a node's own single-key pair (Sec. 3.2 items 1-2).  grid = L.
+//   sk (prepared) [2][L][N] = NTT(s), quotients;  pk (prepared) [2][2][L][N] = (p0, quotients,
+//   p1, quotients) with p1 = NTT(a), a uniform in R_q, p0 = -(p1 s + e).
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_receiver_keygen(uint32_t party, uint64_t *sk, uint64_t *pk,
+                                                            const LimbTab *tabs, RoundConst rc)
+{
+    typedef typename ENG::A A;
+    constexpr int E = ENG::E;
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    uint32_t *lds32 = (uint32_t *)lds;
+    const int tid = threadIdx.x;
+    const uint32_t limb = blockIdx.x, L = rc.L;
+    const LimbTab tb = load_tab(tabs, limb);
+    const uint64_t q = tb.q;
+    const typename A::Mod md = A::mod(q, tb.one_s);
+    const size_t LN = (size_t)L * ENG::NB, off = (size_t)limb * ENG::NB;
+    typename A::elem x[E];
+    // secret key: ternary, counter (block, 0, party, RSK)
+    for (int j = tid; j < ENG::NB / 4; j += ENG::T) {
+        int32_t v[4];
+        ternary4(philox4x32_10(j, 0, party, counter_tag(DOM_RSK, 0, 0), rc.key), v);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lds32[4 * j + i] = (uint32_t)v[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < E; ++k) x[k] = A::from_small((int32_t)lds32[ENG::coef_pos(k, tid)], md);
+    ENG::forward(x, lds, tid, 0, tb.fwd, md);
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+        const int pos = ENG::eval_pos(k, tid);
+        const uint64_t sv = A::canon_fwd(x[k], md);
+        sk[off + pos] = sv;
+        sk[LN + off + pos] = shoup_quotient(sv, q);
+    }
+    // p1: coefficient n is block n of (RPK_A, limb) reduced mod q
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+        const uint32_t n = (uint32_t)ENG::coef_pos(k, tid);
+        x[k] = A::from_canon(uniform_mod(philox4x32_10(n, 0, party, counter_tag(DOM_RPK_A, limb, 0), rc.key), q), md);
+    }
+    ENG::forward(x, lds, tid, 0, tb.fwd, md);
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+        const int pos = ENG::eval_pos(k, tid);
+        const uint64_t av = A::canon_fwd(x[k], md);
+        pk[2 * LN + off + pos] = av;
+        pk[3 * LN + off + pos] = shoup_quotient(av, q);
+    }
+    // error, then p0 = -(p1 s + e) from the values this thread has just stored
+    __syncthreads();
+    stage_cbd<ENG>(lds32, tid, DOM_RPK_E, party, 0, 0, rc);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < E; ++k) x[k] = A::from_small((int32_t)lds32[ENG::coef_pos(k, tid)], md);
+    ENG::forward(x, lds, tid, 0, tb.fwd, md);
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+        const int pos = ENG::eval_pos(k, tid);
+        const typename A::elem prod = A::mul(A::from_canon(sk[off + pos], md),
+                                             A::tw(pk[2 * LN + off + pos], pk[3 * LN + off + pos]), md);
+        const uint64_t sum = A::canon_acc(A::add(prod, x[k]), md);      // p1 s + e
+        const uint64_t p0 = sum == 0 ? 0 : q - sum;
+        pk[off + pos] = p0;
+        pk[LN + off + pos] = shoup_quotient(p0, q);
+    }
+}
+
+// A member's conversion share towards a receiver, Eq. (1), in evaluation form.  grid = (C, jobs).
+//   h0 = s_k c1 + NTT(mu) p0_i + NTT(e0),   h1 = NTT(mu) p1_i + NTT(e1)
+// mu ternary, e0, e1 from chi, counters (block, ciphertext, member | receiver << 16, domain | group << 16).
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_share(ConvJobs jobs, uint32_t ct_base, const LimbTab *tabs,
+                                                          RoundConst rc)
+{
+    typedef typename ENG::A A;
+    typedef typename A::elem elem;
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    uint32_t *lds32 = (uint32_t *)lds;
+    constexpr int E = ENG::E;
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x, job = blockIdx.y, L = rc.L;
+    const size_t LN = (size_t)L * ENG::NB;
+    const uint64_t *sk = jobs.sk[job], *pk = jobs.pk[job];
+    const uint64_t *c1 = jobs.ct[job] + ((size_t)c * 2 + 1) * LN;
+    uint64_t *out = jobs.out[job] + (size_t)c * 2 * LN;
+    uint32_t smp[E];
+    stage_encrypt_samples<ENG>(lds32, tid, DOM_CVT_U, jobs.who[job], jobs.group[job], ct_base + c, rc);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < E; ++k) smp[k] = lds32[ENG::coef_pos(k, tid)];
+
+    for (uint32_t limb = 0; limb < L; ++limb) {
+        const LimbTab tb = load_tab(tabs, limb);
+        const typename A::Mod md = A::mod(tb.q, tb.one_s);
+        const size_t off = (size_t)limb * ENG::NB;
+        const int tl = opaque(tid);
+        // as in Encrypt: with 16 coefficients per thread NTT(mu) is parked in the h1 slot of the output
+        constexpr bool STASH = E > 8;
+        uint64_t *stash = out + LN + off;
+        elem u[E];
+#pragma unroll
+        for (int k = 0; k < E; ++k) u[k] = A::from_small(sbyte(opaque(smp[k]), 0), md);
+        ENG::forward(u, lds, tl, 0, tb.fwd, md);
+        if (STASH) {
+#pragma unroll
+            for (int k = 0; k < E; ++k) st64(stash, 8u * (uint32_t)tl, 8u * ENG::T * k, to_bits<A>(u[k]));
+        }
+        elem x[E];
+#pragma unroll
+        for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(opaque(smp[k]), 1), md);
+        ENG::forward(x, lds, opaque(tl), 0, tb.fwd, md);
+        {
+            // h0: two products per slot, each reduced on its own
+            typename A::Twid kv[E];
+#pragma unroll
+            for (int k = 0; k < E; ++k) kv[k] = A::key(sk + off, sk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
+#pragma unroll
+            for (int k = 0; k < E; ++k) {
+                const uint64_t cv = ld64(c1 + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
+                x[k] = A::from_canon(A::canon_acc(A::add(A::mul(A::from_canon(cv, md), kv[k], md), x[k]), md), md);
+            }
+#pragma unroll
+            for (int k = 0; k < E; ++k) kv[k] = A::key(pk + off, pk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
+#pragma unroll
+            for (int k = 0; k < E; ++k) {
+                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
+                const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k];
+                st64(out + off, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k]), md));
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(opaque(smp[k]), 2), md);
+        ENG::forward(x, lds, opaque(tl), 0, tb.fwd, md);
+        {
+            typename A::Twid kv[E];
+#pragma unroll
+            for (int k = 0; k < E; ++k)
+                kv[k] = A::key(pk + 2 * LN + off, pk + 3 * LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
+#pragma unroll
+            for (int k = 0; k < E; ++k) {
+                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
+                const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k];
+                st64(stash, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k]), md));
+            }
+        }
+    }
+}
+
+// The receiver's side of MBFV.Convert fused with BFV.Decrypt(sk_i, .) (Eq. (2)); grid = C.
+// Plaintext polynomials out.  K = 0 and keep_c1: plain single-key decryption of `ct`.
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_combine(const uint64_t *ct, PtrList shares, uint32_t K,
+                                                            const uint64_t *skr, int keep_c1, uint64_t *pt,
+                                                            const LimbTab *tabs, RoundConst rc)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    combine_body<ENG, false, true>(lds, ct, [&](uint32_t j) { return (const uint64_t *)shares.p[j]; }, K, skr,
+                                   keep_c1 != 0, pt, (float *)nullptr, 0, tabs, rc);
+}
+
+// whole round: grid = (C, receivers of all groups); decoded floats out
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_combine_decode(RecvJobs jobs, size_t stride,
+                                                                   uint64_t n_values, const LimbTab *tabs,
+                                                                   RoundConst rc)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    const uint32_t job = blockIdx.y;
+    const uint64_t *first = jobs.first[job];
+    combine_body<ENG, true, true>(lds, jobs.ct[job], [&](uint32_t j) { return first + (size_t)j * stride; },
+                                  jobs.K[job], jobs.sk[job], false, (uint64_t *)nullptr, (float *)jobs.out[job],
+                                  n_values, tabs, rc);
 }
 
 }  // namespace d2

@@ -14,7 +14,10 @@ namespace d2 {
 
 enum : uint32_t {
     DOM_SK = 1, DOM_PK_E = 2, DOM_CRS = 3, DOM_ENC_U = 4, DOM_ENC_E0 = 5, DOM_ENC_E1 = 6,
-    DOM_DEC_E = 7, DOM_BENCH = 8
+    DOM_DEC_E = 7, DOM_BENCH = 8,
+    // MBFV.Convert: a receiver's own key pair and the randomness of a conversion share (mu, e0, e1
+    // consecutive, like the three domains of Encrypt)
+    DOM_RSK = 0x10, DOM_RPK_A = 0x11, DOM_RPK_E = 0x12, DOM_CVT_U = 0x13, DOM_CVT_E0 = 0x14, DOM_CVT_E1 = 0x15
 };
 
 struct PhiloxKey { uint32_t k0, k1; };

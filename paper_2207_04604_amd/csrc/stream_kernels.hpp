@@ -53,6 +53,26 @@ __global__ void __launch_bounds__(256) k_sum(uint64_t *dst, PtrList src, uint32_
     *(ulonglong2 *)(dst + i) = acc;
 }
 
+// MBFV.Convert: dst = (c0 + sum_k h0_k, sum_k h1_k) over [C][2][L][N]; the c1 of ct is dropped.
+// LN = L * N words per component.
+__global__ void __launch_bounds__(256) k_convert_sum(uint64_t *dst, const uint64_t *ct, PtrList src, uint32_t K,
+                                                     const LimbTab *tabs, uint32_t L, uint32_t log2n, size_t LN,
+                                                     size_t total)
+{
+    size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 2;
+    if (i >= total) return;
+    uint64_t q = tabs[(i >> log2n) % L].q;
+    ulonglong2 acc;
+    if ((i / LN) & 1) { acc.x = 0; acc.y = 0; }
+    else acc = *(const ulonglong2 *)(ct + i);
+    for (uint32_t k = 0; k < K; ++k) {
+        ulonglong2 v = *(const ulonglong2 *)((const uint64_t *)src.p[k] + i);
+        acc.x = add_mod(acc.x, v.x, q);
+        acc.y = add_mod(acc.y, v.y, q);
+    }
+    *(ulonglong2 *)(dst + i) = acc;
+}
+
 // Whole round: out[g] = sum of the K_g ciphertext buffers of group g (stride words apart).
 // grid = (ceil(words / 512), groups); `words` = C * 2 * L * N per buffer.
 __global__ void __launch_bounds__(256) k_sum_groups(GroupJobs jobs, size_t stride, const LimbTab *tabs, uint32_t L,

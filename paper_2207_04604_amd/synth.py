@@ -75,6 +75,15 @@ class Config:
         members sorted by party id."""
         return closed_neighbourhood_groups(self.adjacency())[0]
 
+    def receivers(self) -> List[List[int]]:
+        """For every group, the nodes whose closed neighbourhood it is: the receivers of its sum
+        (one node per group on the circulant graphs, every node on a complete graph)."""
+        groups, owner = closed_neighbourhood_groups(self.adjacency())
+        out = [[] for _ in groups]
+        for i, g in enumerate(owner):
+            out[g].append(i)
+        return out
+
     @property
     def max_group(self) -> int:
         gs = self.groups()
