@@ -5,7 +5,11 @@ A step is one whole round of the hot path (encode + encrypt, homomorphic sum, de
 shares, combine + decode) for every group of the workload, with the float32 gradients and
 all keys already resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu] [--no-ntt]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu] [--no-ntt] [--no-convert]
+
+Beside the headline round it reports the same round with the paper's own decryption path
+(key switching of every aggregate to its receivers, MBFV.Convert), the batched transform
+micro-benchmark, and the CPU oracle timed on a bounded sample.
 """
 import argparse
 import json
@@ -44,6 +48,8 @@ def main():
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-ntt", action="store_true", help="skip the transform micro-benchmark")
+    ap.add_argument("--no-convert", action="store_true",
+                    help="skip the round with key switching to the receivers (MBFV.Convert)")
     ap.add_argument("--ntt-reps", type=int, default=20)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain device copies of 512 MiB (reference for the HBM byte counters)")
@@ -177,6 +183,52 @@ def main():
                      "hbm_algorithmic_GB_per_s": enc_bytes / 1e9 / (enc_ms * 1e-3),
                      "hbm_frac": enc_bytes / 1e9 / (enc_ms * 1e-3) / HBM_PEAK_GBS},
     }
+
+    # ---- the same round with MBFV.Convert: every node receives the sum of its closed neighbourhood
+    # under its own key (three transforms per limb and share instead of one, two polynomials per share)
+    if not args.no_convert:
+        receivers = cfg.receivers()
+        R = sum(len(r) for r in receivers)
+        rsk = [dz(2 * L * N) for _ in range(P)]
+        rpk = [dz(4 * L * N) for _ in range(P)]
+        for k in range(P):
+            ctx.receiver_keygen(k, rsk[k], rpk[k], sptr)
+        routs = [torch.zeros(cfg.n_values, dtype=torch.float32, device=dev) for _ in range(R)]
+        conv = ctx.make_convert(desc, receivers, rpk, rsk, routs)
+        cbytes = ctx.round_convert_scratch_bytes(J, G, conv.num_shares, cfg.n_values)
+        del scratch
+        cscratch = dz(cbytes // 8)
+        csteps = max(1, min(args.steps, 10))
+        for _ in range(min(args.warmup, 2)):
+            ctx.round_convert(desc, conv, cscratch, cbytes, None, sptr)
+        torch.cuda.synchronize()
+        cev = [new_events() for _ in range(csteps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(csteps):
+            ctx.round_convert(desc, conv, cscratch, cbytes, [e.cuda_event for e in cev[i]], sptr)
+        torch.cuda.synchronize()
+        cms = (time.perf_counter() - t0) * 1e3 / csteps
+        cphase = [sum(ev[i].elapsed_time(ev[i + 1]) for ev in cev) / csteps for i in range(4)]
+        ri = 0
+        for gi in range(G):
+            for _ in receivers[gi]:
+                if gi in (0, G - 1):
+                    acc = np.zeros(cfg.n_values, dtype=np.int64)
+                    for k in groups[gi]:
+                        acc += np.clip(np.rint(grads_host[k] * np.float32(2.0 ** cfg.frac_bits)), -clamp, clamp).astype(np.int64)
+                    if not np.array_equal(routs[ri].cpu().numpy(), acc.astype(np.float32) * np.float32(2.0 ** -cfg.frac_bits)):
+                        print("bench.py: converted result differs from the fixed-point sum", file=sys.stderr)
+                        sys.exit(6)
+                ri += 1
+        result["convert_round"] = {
+            "what": "encode+encrypt, sum, conversion shares towards every receiver (Eq. (1)), "
+                    "converted ciphertext + single-key decryption + decode (Eq. (2))",
+            "receivers": R, "conversion_shares": conv.num_shares, "ms_per_step": cms, "steps": csteps,
+            "fresh_ct_per_s": fresh / (cms * 1e-3),
+            "phase_ms": {"encode_encrypt": cphase[0], "aggregate": cphase[1], "convert_shares": cphase[2],
+                         "combine_decrypt_decode": cphase[3]}}
+        del cscratch
 
     # ---- transform micro-benchmark: forward + inverse, N = 65536, 16 limbs, batch 64 ------
     if not args.no_ntt:
