@@ -29,7 +29,7 @@ VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz = 39.3
 # HBM bytes of one launch of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by
 # a plain 512 MiB device copy (profiles/k_encrypt_C2_round_and_ntt_C5.txt); only for the
 # workload that was profiled.
-MEASURED_TRAFFIC_BYTES = {"C2": 64.9e6 + 393.2e6}
+MEASURED_TRAFFIC_BYTES = {"C2": 73.0e6 + 393.2e6}
 
 
 def ops_per_butterfly(qmax):
