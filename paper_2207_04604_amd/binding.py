@@ -160,9 +160,9 @@ class Context:
         self.q = [int(v) for v in q]
 
     def close(self):
-        if getattr(self, "_h", None):
-            lib().d2mhe_destroy(self._h)
-            self._h = None
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.d2mhe_destroy(self._h)
+        self._h = None
 
     def __del__(self):
         self.close()

@@ -16,30 +16,25 @@ struct Launch {
                 hipLaunchKernelGGL(k_ntt_inverse<ENG>, dim3(polys_n), dim3(ENG::T), 0, st, polys, ctx->d_tabs, L);
             D2_LAUNCHED(ctx);
         } else {
-            // head: top stages across blocks; tail: one workgroup per block.  The batch is walked in
-            // chunks of polynomials that fit the second grid dimension.
+            // head: top stages across blocks; tail: the block-local stages.  The batch is walked in
+            // chunks of whole batches that fit the second grid dimension of the head kernel.
             constexpr int LOGN = ENG::LOGN, LOGH = LOGN - ENG::LOGB;
-            const uint32_t chunk_polys = ctx->ntt_chunk_polys ? ctx->ntt_chunk_polys : polys_n;
-            for (uint32_t p0 = 0; p0 < polys_n; p0 += chunk_polys) {
-                const uint32_t n = polys_n - p0 < chunk_polys ? polys_n - p0 : chunk_polys;
-                uint64_t *base = polys + ((size_t)p0 << LOGN);
-                // limb of polynomial p = (p0 + p) % L: pass the offset so that the kernels see it
-                // tail: TAIL_TILES tiles per workgroup; the grid is kept a multiple of 8 when the
-                // tile count is one, so that launch index and workgroup share their XCD
-                const uint32_t tiles = (1u << LOGH) * n;
-                uint32_t tgrid_x = (tiles + TAIL_TILES - 1) / TAIL_TILES;
-                if ((tiles & 7u) == 0) tgrid_x = (tgrid_x + 7u) & ~7u;
-                dim3 hgrid((1u << (LOGN - LOGH)) / 256, n), tgrid(tgrid_x);
+            const uint32_t chunk_b = ctx->ntt_chunk_polys / L ? ctx->ntt_chunk_polys / L : 1;
+            for (uint32_t b0 = 0; b0 < B; b0 += chunk_b) {
+                const uint32_t nb = B - b0 < chunk_b ? B - b0 : chunk_b, n = nb * L;
+                uint64_t *base = polys + ((size_t)b0 * L << LOGN);
+                dim3 hgrid((1u << (LOGN - LOGH)) / 256, n);
+                dim3 tgrid(L * (1u << LOGH) * ((nb + TAIL_TILES - 1) / TAIL_TILES));
                 if (forward) {
                     hipLaunchKernelGGL((k_head_forward<typename ENG::A, LOGN, LOGH>), hgrid, dim3(256), 0, st, base,
-                                       ctx->d_tabs, L, p0);
+                                       ctx->d_tabs, L, 0u);
                     D2_LAUNCHED(ctx);
-                    hipLaunchKernelGGL(k_tail_forward<ENG>, tgrid, dim3(ENG::T), 0, st, base, ctx->d_tabs, L, p0, n, tiles);
+                    hipLaunchKernelGGL(k_tail_forward<ENG>, tgrid, dim3(ENG::T), 0, st, base, ctx->d_tabs, L, nb);
                 } else {
-                    hipLaunchKernelGGL(k_tail_inverse<ENG>, tgrid, dim3(ENG::T), 0, st, base, ctx->d_tabs, L, p0, n, tiles);
+                    hipLaunchKernelGGL(k_tail_inverse<ENG>, tgrid, dim3(ENG::T), 0, st, base, ctx->d_tabs, L, nb);
                     D2_LAUNCHED(ctx);
                     hipLaunchKernelGGL((k_head_inverse<typename ENG::A, LOGN, LOGH>), hgrid, dim3(256), 0, st, base,
-                                       ctx->d_tabs, L, p0);
+                                       ctx->d_tabs, L, 0u);
                 }
                 D2_LAUNCHED(ctx);
             }

@@ -226,71 +226,63 @@ __global__ void __launch_bounds__(256) k_head_inverse(uint64_t *polys, const Lim
     for (int k = 0; k < H; ++k) p[(size_t)k * STRIDE] = A::canon_inv(x[k], md);
 }
 
-// Tiles that share twiddles -- the same (limb, block) of every polynomial of the batch -- should
-// run back to back on the same XCD, whose L2 then serves the 64 KB of twiddles to all of them
-// (workgroups are handed to the 8 XCDs round-robin by linear id).  Launch order i -> slot:
-// XCD x = i % 8 walks the contiguous slot range [x * total/8, (x+1) * total/8); slot -> (group =
-// limb * blocks + block, member = batch index).  Returns the polynomial index (b * L + limb)
-// within this launch and the block.
-D2_DEV void tail_tile(uint32_t i, uint32_t total, uint32_t polys, uint32_t L, uint32_t nblk, uint32_t poly0,
-                      uint32_t &poly, uint32_t &blk)
+// Tail of a long transform over polys [B][L][N].  Tiles that share twiddles -- the same (limb, block)
+// of every polynomial of the batch, a "group" of B members -- are given to one workgroup TAIL_TILES
+// members at a time: it fetches the twiddles once (scalar registers for the uniform passes, 56
+// vector registers for the rest with 16-byte entries) and walks its members with the next member's
+// coefficients already requested.  Without this the twiddles are twice the bytes of the data.
+// Workgroups are handed to the 8 XCDs round-robin by linear id: XCD x = i % 8 walks the contiguous
+// slot range [x * grid/8, (x+1) * grid/8), so that the workgroups of a group also share an L2.
+constexpr int TAIL_TILES = 8;
+
+struct TailTile {
+    uint32_t limb, blk, m0, m1;       // members [m0, m1) of group (limb, blk)
+};
+D2_DEV TailTile tail_tile(uint32_t i, uint32_t grid, uint32_t B, uint32_t nblk)
 {
+    const uint32_t wpg = (B + TAIL_TILES - 1) / TAIL_TILES;      // workgroups per group
     uint32_t slot = i;
-    if ((total & 7u) == 0) slot = (i & 7u) * (total >> 3) + (i >> 3);
-    // members of a group: polynomials of this launch with the same limb
-    const uint32_t B = polys / L;                 // whole batches in this launch (polys = B * L + rest)
-    const uint32_t grouped = B * L * nblk;        // slots covered by whole batches
-    if (B == 0 || slot >= grouped) {              // leftovers: plain order
-        poly = slot / nblk;
-        blk = slot % nblk;
-        return;
-    }
-    const uint32_t group = slot / B, member = slot % B;
-    const uint32_t limb_pos = group / nblk;       // position of the limb inside a batch of this launch
-    blk = group % nblk;
-    poly = member * L + limb_pos;
-    (void)poly0;
+    if ((grid & 7u) == 0) slot = (i & 7u) * (grid >> 3) + (i >> 3);
+    const uint32_t group = slot / wpg, part = slot % wpg;
+    // the same in every lane (they depend on the workgroup id only): keep them in scalar registers,
+    // the divisions above went through the vector ALU
+    TailTile t;
+    t.limb = wave_uniform(group / nblk);
+    t.blk = wave_uniform(group % nblk);
+    t.m0 = wave_uniform(part * TAIL_TILES);
+    t.m1 = t.m0 + TAIL_TILES < B ? t.m0 + TAIL_TILES : B;
+    return t;
 }
 
-// tail: every workgroup walks TAIL_TILES tiles, launch index v = blockIdx.x + i * gridDim.x (see
-// tail_tile for the tile of a launch index; with a grid that is a multiple of 8 a workgroup stays
-// on the twiddles of its XCD).  The coefficients of the next tile are requested before the current
-// one is transformed, so a wave always has a full tile of loads in flight behind its arithmetic.
-constexpr int TAIL_TILES = 4;
-
+// grid = L * 2^(LOGN - LOGB) * ceil(B / TAIL_TILES)
 template <class ENG>
 __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_forward(uint64_t *polys, const LimbTab *tabs, uint32_t L,
-                                                        uint32_t poly0, uint32_t npolys, uint32_t total)
+                                                        uint32_t B)
 {
     typedef typename ENG::A A;
     constexpr int E = ENG::E;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
-    const uint32_t nblk = 1u << (ENG::LOGN - ENG::LOGB);
-    uint32_t poly, blk;
+    const TailTile tt = tail_tile(blockIdx.x, gridDim.x, B, 1u << (ENG::LOGN - ENG::LOGB));
+    if (tt.limb >= L || tt.m0 >= tt.m1) return;
+    const LimbTab tb = load_tab(tabs, tt.limb);
+    const typename A::Mod md = A::mod(tb.q, tb.one_s);
+    typename ENG::Twiddles tw;
+    ENG::template load_all<false, false>(tw, tid, tt.blk, tb.fwd);
+    const size_t stride = (size_t)L << ENG::LOGN;        // words between members
+    uint64_t *p = polys + ((size_t)tt.m0 * L + tt.limb << ENG::LOGN) + ((size_t)tt.blk << ENG::LOGB);
     uint64_t nx[E];
-    if (blockIdx.x >= total) return;
-    tail_tile(blockIdx.x, total, npolys, L, nblk, poly0, poly, blk);
-    {
-        const uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
 #pragma unroll
-        for (int k = 0; k < E; ++k) nx[k] = ld64(p, 8u * (uint32_t)tid, 8u * ENG::T * k);
-    }
-    for (uint32_t v = blockIdx.x; v < total; v += gridDim.x) {
-        const LimbTab tb = load_tab(tabs, (poly0 + poly) % L);
-        const typename A::Mod md = A::mod(tb.q, tb.one_s);
-        uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
-        const uint32_t cur_blk = blk;
+    for (int k = 0; k < E; ++k) nx[k] = ld64(p, 8u * (uint32_t)tid, 8u * ENG::T * k);
+    for (uint32_t m = tt.m0; m < tt.m1; ++m, p += stride) {
         typename A::elem x[E];
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = from_bits<A>(nx[k]);
-        if (v + gridDim.x < total) {
-            tail_tile(v + gridDim.x, total, npolys, L, nblk, poly0, poly, blk);
-            const uint64_t *pn = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
+        if (m + 1 < tt.m1) {
 #pragma unroll
-            for (int k = 0; k < E; ++k) nx[k] = ld64(pn, 8u * (uint32_t)tid, 8u * ENG::T * k);
+            for (int k = 0; k < E; ++k) nx[k] = ld64(p + stride, 8u * (uint32_t)tid, 8u * ENG::T * k);
         }
-        ENG::forward(x, lds, tid, cur_blk, tb.fwd, md);
+        ENG::forward(x, lds, tid, tw, md);
 #pragma unroll
         for (int k = 0; k < E; ++k) st64(p, 8u * (uint32_t)tid, 8u * ENG::T * k, A::canon_fwd(x[k], md));
     }
@@ -298,37 +290,33 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_forward(uint64_t *p
 
 template <class ENG>
 __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_inverse(uint64_t *polys, const LimbTab *tabs, uint32_t L,
-                                                        uint32_t poly0, uint32_t npolys, uint32_t total)
+                                                        uint32_t B)
 {
     typedef typename ENG::A A;
     constexpr int E = ENG::E;
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const int tid = threadIdx.x;
-    const uint32_t nblk = 1u << (ENG::LOGN - ENG::LOGB);
-    uint32_t poly, blk;
+    const TailTile tt = tail_tile(blockIdx.x, gridDim.x, B, 1u << (ENG::LOGN - ENG::LOGB));
+    if (tt.limb >= L || tt.m0 >= tt.m1) return;
+    const LimbTab tb = load_tab(tabs, tt.limb);
+    const typename A::Mod md = A::mod(tb.q, tb.one_s);
+    typename ENG::Twiddles tw;
+    ENG::template load_all<true, false>(tw, tid, tt.blk, tb.inv);
+    const typename A::Twid ninv = A::tw(tb.ninv), wn = A::tw(tb.wn);
+    const size_t stride = (size_t)L << ENG::LOGN;
+    uint64_t *p = polys + ((size_t)tt.m0 * L + tt.limb << ENG::LOGN) + ((size_t)tt.blk << ENG::LOGB);
     uint64_t nx[E];
-    if (blockIdx.x >= total) return;
-    tail_tile(blockIdx.x, total, npolys, L, nblk, poly0, poly, blk);
-    {
-        const uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
 #pragma unroll
-        for (int k = 0; k < E; ++k) nx[k] = ld64(p, 8u * (uint32_t)tid, 8u * ENG::T * k);
-    }
-    for (uint32_t v = blockIdx.x; v < total; v += gridDim.x) {
-        const LimbTab tb = load_tab(tabs, (poly0 + poly) % L);
-        const typename A::Mod md = A::mod(tb.q, tb.one_s);
-        uint64_t *p = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
-        const uint32_t cur_blk = blk;
+    for (int k = 0; k < E; ++k) nx[k] = ld64(p, 8u * (uint32_t)tid, 8u * ENG::T * k);
+    for (uint32_t m = tt.m0; m < tt.m1; ++m, p += stride) {
         typename A::elem x[E];
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = A::inv_input(nx[k], md);
-        if (v + gridDim.x < total) {
-            tail_tile(v + gridDim.x, total, npolys, L, nblk, poly0, poly, blk);
-            const uint64_t *pn = polys + ((size_t)poly << ENG::LOGN) + ((size_t)blk << ENG::LOGB);
+        if (m + 1 < tt.m1) {
 #pragma unroll
-            for (int k = 0; k < E; ++k) nx[k] = ld64(pn, 8u * (uint32_t)tid, 8u * ENG::T * k);
+            for (int k = 0; k < E; ++k) nx[k] = ld64(p + stride, 8u * (uint32_t)tid, 8u * ENG::T * k);
         }
-        ENG::template inverse<false>(x, lds, tid, cur_blk, tb.inv, md, A::tw(tb.ninv), A::tw(tb.wn));
+        ENG::template inverse<false>(x, lds, tid, tw, md, ninv, wn);
 #pragma unroll
         for (int k = 0; k < E; ++k) st64(p, 8u * (uint32_t)tid, 8u * ENG::T * k, to_bits<A>(x[k]));   // lazy, head finishes
     }

@@ -291,6 +291,48 @@ struct Engine {
         fwd_from<0>(x, w, lds, tid, blk, tw, md);
     }
 
+    // All twiddles of one transform, for callers that run several transforms with the same table and
+    // block id: fetched once, they stay in registers (scalar registers for the uniform passes).
+    // Only for shapes whose passes all take their twiddles as a set.
+    struct Twiddles {
+        Twid w[NPASS][E];
+    };
+    template <int P = 0>
+    static constexpr bool all_ahead() { return ahead<P>() && (P + 1 == NPASS || all_ahead<(P + 1 < NPASS ? P + 1 : P)>()); }
+
+    template <bool INV, bool FOLD, int P = 0>
+    D2_DEV static void load_all(Twiddles &t, int tid, uint32_t blk, const Tw *tw)
+    {
+        load_tw<P, FOLD, !INV>(t.w[P], tid, blk, tw);
+        if constexpr (P + 1 < NPASS) load_all<INV, FOLD, P + 1>(t, tid, blk, tw);
+    }
+
+    template <int P = 0>
+    D2_DEV static void forward(elem (&x)[E], uint64_t *lds, int tid, const Twiddles &t, const Mod &md)
+    {
+        static_assert(ahead<P>(), "shape loads twiddles stage by stage");
+        fwd_pass<P>(x, t.w[P], tid, 0, nullptr, md);
+        if constexpr (P + 1 < NPASS) {
+            exchange<P, P + 1>(x, lds, tid);
+            forward<P + 1>(x, lds, tid, t, md);
+        }
+    }
+
+    template <bool FOLD, int P = NPASS - 1>
+    D2_DEV static void inverse(elem (&x)[E], uint64_t *lds, int tid, const Twiddles &t, const Mod &md,
+                               const Twid &ninv, const Twid &wn)
+    {
+        static_assert(ahead<P>(), "shape loads twiddles stage by stage");
+        if constexpr (P == NPASS - 1 && NPASS > 1) {
+            if (intra_wave<NPASS - 1, NPASS - 2>()) __syncthreads();
+        }
+        inv_pass<P, FOLD>(x, t.w[P], tid, 0, nullptr, md, ninv, wn);
+        if constexpr (P > 0) {
+            exchange<P, P - 1>(x, lds, tid);
+            inverse<FOLD, P - 1>(x, lds, tid, t, md, ninv, wn);
+        }
+    }
+
     // x: last-pass ownership (canonical input) -> pass-0 ownership, lazy; scaled by N^-1 when FOLD.
     // The first exchange of an inverse transform stays inside the wave and therefore has no
     // barrier of its own: the one here covers readers in other waves (of staged inputs, or of the
