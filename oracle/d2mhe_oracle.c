@@ -775,6 +775,76 @@ void orc_convert_combine(const orc_ctx *c, const uint64_t *ct, const uint64_t *c
         }
 }
 
+/* ---- MBFV.Bootstrap (Sec. 4.2 item 4, Eq. (3)) ---- */
+
+void orc_bootstrap_alpha(const orc_ctx *c, uint32_t group, uint32_t ct, uint64_t *alpha)
+{
+    for (uint32_t i = 0; i < c->p.num_limbs; ++i)
+        orc_sample_uniform(c->p.seed, ORC_DOM_BS_A, i, 0, group, ct, c->p.q[i], c->n, alpha + (size_t)i * c->n);
+}
+
+void orc_bootstrap_share(const orc_ctx *c, const uint64_t *sk_share, const uint64_t *ct, uint32_t C,
+                         uint32_t party, uint32_t group, uint32_t ct_base, uint64_t *share)
+{
+    size_t n = c->n;
+    uint32_t L = c->p.num_limbs;
+    uint64_t *M = (uint64_t *)malloc(n * sizeof(uint64_t));
+    int32_t *e0 = (int32_t *)malloc(n * sizeof(int32_t));
+    int32_t *e1 = (int32_t *)malloc(n * sizeof(int32_t));
+    uint64_t *alpha = (uint64_t *)malloc((size_t)L * n * sizeof(uint64_t));
+    uint64_t *sc1 = (uint64_t *)malloc(n * sizeof(uint64_t));
+    uint64_t *sa = (uint64_t *)malloc(n * sizeof(uint64_t));
+    for (uint32_t ci = 0; ci < C; ++ci) {
+        uint32_t index = ct_base + ci;
+        orc_sample_uniform(c->p.seed, ORC_DOM_BS_M, 0, party, group, index, c->p.t, n, M);
+        orc_sample_cbd(c->p.seed, ORC_DOM_BS_E0, party, group, index, c->p.cbd_eta, n, e0);
+        orc_sample_cbd(c->p.seed, ORC_DOM_BS_E1, party, group, index, c->p.cbd_eta, n, e1);
+        orc_bootstrap_alpha(c, group, index, alpha);
+        const uint64_t *c1 = ct + ((size_t)ci * 2 + 1) * L * n;
+        uint64_t *eta0 = share + (size_t)ci * 2 * L * n;
+        uint64_t *eta1 = eta0 + (size_t)L * n;
+        for (uint32_t i = 0; i < L; ++i) {
+            uint64_t q = c->p.q[i];
+            const uint64_t *ski = sk_share + (size_t)i * n;
+            orc_ring_mul(ski, c1 + (size_t)i * n, n, q, c->psi[i], sc1);
+            orc_ring_mul(ski, alpha + (size_t)i * n, n, q, c->psi[i], sa);
+            for (size_t k = 0; k < n; ++k) {
+                uint64_t lm = orc_mulmod(c->lambda_mod_q[i], M[k] % q, q); /* Lambda M_k */
+                eta0[(size_t)i * n + k] = addmod(submod(sc1[k], lm, q), lift_small(e0[k], q), q);
+                eta1[(size_t)i * n + k] = addmod(submod(lm, sa[k], q), lift_small(e1[k], q), q);
+            }
+        }
+    }
+    free(M); free(e0); free(e1); free(alpha); free(sc1); free(sa);
+}
+
+void orc_bootstrap_combine(const orc_ctx *c, const uint64_t *ct, const uint64_t *const *shares,
+                           uint32_t K, uint32_t C, uint32_t group, uint32_t ct_base, uint64_t *ct_out)
+{
+    size_t n = c->n;
+    uint32_t L = c->p.num_limbs;
+    for (uint32_t ci = 0; ci < C; ++ci) {
+        size_t base = (size_t)ci * 2 * L * n;
+        for (size_t k = 0; k < n; ++k) {
+            uint64_t res[ORC_MAX_LIMBS];
+            for (uint32_t i = 0; i < L; ++i) {
+                uint64_t acc = ct[base + (size_t)i * n + k];              /* c0 + eta0 */
+                for (uint32_t m = 0; m < K; ++m) acc = addmod(acc, shares[m][base + (size_t)i * n + k], c->p.q[i]);
+                res[i] = acc;
+            }
+            uint64_t x = scale_round(c, res);                              /* in [0,t) */
+            for (uint32_t i = 0; i < L; ++i) {
+                uint64_t q = c->p.q[i];
+                uint64_t acc = orc_mulmod(c->lambda_mod_q[i], x % q, q);  /* Lambda x + eta1 */
+                for (uint32_t m = 0; m < K; ++m)
+                    acc = addmod(acc, shares[m][base + (size_t)(L + i) * n + k], q);
+                ct_out[base + (size_t)i * n + k] = acc;
+            }
+        }
+        orc_bootstrap_alpha(c, group, ct_base + ci, ct_out + base + (size_t)L * n);
+    }
+}
+
 void orc_bench_polys(const orc_ctx *c, uint32_t B, uint64_t *out)
 {
     for (uint32_t b = 0; b < B; ++b)

@@ -45,7 +45,12 @@ enum {
     ORC_DOM_RPK_E = 0x12,  /* error of a receiver's public key         */
     ORC_DOM_CVT_U = 0x13,  /* mu_k of a conversion share               */
     ORC_DOM_CVT_E0 = 0x14, /* e0_k of a conversion share               */
-    ORC_DOM_CVT_E1 = 0x15  /* e1_k of a conversion share               */
+    ORC_DOM_CVT_E1 = 0x15, /* e1_k of a conversion share               */
+    /* MBFV.Bootstrap (Sec. 4.2 item 4) */
+    ORC_DOM_BS_M = 0x16,   /* mask M_k, uniform in R_t                 */
+    ORC_DOM_BS_E0 = 0x17,  /* e0_k of a bootstrap share                */
+    ORC_DOM_BS_E1 = 0x18,  /* e1_k of a bootstrap share                */
+    ORC_DOM_BS_A = 0x19    /* common random polynomial alpha (per limb) */
 };
 
 typedef struct {
@@ -152,6 +157,22 @@ void orc_convert_share(const orc_ctx *c, const uint64_t *sk_share, const uint64_
  * BFV.Decrypt(sk_i, E') is orc_decrypt_with_secret (Eq. (2)).                            */
 void orc_convert_combine(const orc_ctx *c, const uint64_t *ct, const uint64_t *const *shares,
                          uint32_t K, uint32_t C, uint64_t *ct_out);
+
+/* ---- MBFV.Bootstrap: collective refresh of a ciphertext (Sec. 4.2 item 4, Eq. (3)) ---- */
+/* The common random polynomial alpha of the refresh of ciphertext index ct of a group:
+ * uniform in R_q, alpha [L][N]; counter (block, ct, 0, BS_A | limb << 8 | group << 16).    */
+void orc_bootstrap_alpha(const orc_ctx *c, uint32_t group, uint32_t ct, uint64_t *alpha);
+/* Member k's share, Eq. (3):
+ *   (eta0, eta1) = (s_k c1 - Lambda M_k + e0_k, -s_k alpha + Lambda M_k + e1_k),  share [C][2][L][N],
+ * M_k uniform in R_t (coefficient n = the 128-bit block n reduced mod t, representative in
+ * [0,t)), e0_k, e1_k from chi; counters (block, ct_base + c, k, domain | group << 16).      */
+void orc_bootstrap_share(const orc_ctx *c, const uint64_t *sk_share, const uint64_t *ct, uint32_t C,
+                         uint32_t party, uint32_t group, uint32_t ct_base, uint64_t *share);
+/* The refreshed ciphertext ct' = ([round(t/q [c0 + eta0]_q)]_t Lambda + eta1, alpha) with
+ * eta_d = sum_k eta_{d,k}; the rounded plaintext enters with its representative in [0,t).
+ * ct_out [C][2][L][N].                                                                    */
+void orc_bootstrap_combine(const orc_ctx *c, const uint64_t *ct, const uint64_t *const *shares,
+                           uint32_t K, uint32_t C, uint32_t group, uint32_t ct_base, uint64_t *ct_out);
 
 /* Uniform benchmark polynomials: out [B][L][N], polynomial b of the batch, limb i.      */
 void orc_bench_polys(const orc_ctx *c, uint32_t B, uint64_t *out);

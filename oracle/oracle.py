@@ -83,6 +83,9 @@ def lib():
             "orc_receiver_keygen": (None, [vp, u32, vp, vp, vp, vp]),
             "orc_convert_share": (None, [vp, vp, vp, vp, u32, u32, u32, u32, u32, vp]),
             "orc_convert_combine": (None, [vp, vp, vp, u32, u32, vp]),
+            "orc_bootstrap_alpha": (None, [vp, u32, u32, vp]),
+            "orc_bootstrap_share": (None, [vp, vp, vp, u32, u32, u32, u32, vp]),
+            "orc_bootstrap_combine": (None, [vp, vp, vp, u32, u32, u32, u32, vp]),
             "orc_bench_polys": (None, [vp, u32, vp]),
             "orc_ntt_forward_batch": (None, [vp, vp, u32]),
             "orc_ntt_inverse_batch": (None, [vp, vp, u32]),
@@ -319,6 +322,26 @@ class Oracle:
         shares = [_u64(s) for s in shares]
         out = np.zeros_like(ct)
         lib().orc_convert_combine(self._h, _p(ct), _ptr_array(shares), len(shares), ct.shape[0], _p(out))
+        return out
+
+    # ---- MBFV.Bootstrap (Sec. 4.2 item 4) ----
+    def bootstrap_alpha(self, group, ct):
+        out = np.zeros((self.L, self.N), dtype=np.uint64)
+        lib().orc_bootstrap_alpha(self._h, group, ct, _p(out))
+        return out
+
+    def bootstrap_share(self, sk_share, ct, party, group, ct_base=0):
+        sk_share, ct = _u64(sk_share), _u64(ct)
+        share = np.zeros_like(ct)
+        lib().orc_bootstrap_share(self._h, _p(sk_share), _p(ct), ct.shape[0], party, group, ct_base, _p(share))
+        return share
+
+    def bootstrap_combine(self, ct, shares, group, ct_base=0):
+        ct = _u64(ct)
+        shares = [_u64(s) for s in shares]
+        out = np.zeros_like(ct)
+        lib().orc_bootstrap_combine(self._h, _p(ct), _ptr_array(shares), len(shares), ct.shape[0], group, ct_base,
+                                    _p(out))
         return out
 
     def bench_polys(self, B):

@@ -80,7 +80,8 @@ class PyBFV:
     """Multiparty BFV over Z_Q (Q = prod q_i), straight from Sec. 3.2 and Sec. 4.2."""
 
     DOM = dict(SK=1, PK_E=2, CRS=3, ENC_U=4, ENC_E0=5, ENC_E1=6, DEC_E=7,
-               RSK=0x10, RPK_A=0x11, RPK_E=0x12, CVT_U=0x13, CVT_E0=0x14, CVT_E1=0x15)
+               RSK=0x10, RPK_A=0x11, RPK_E=0x12, CVT_U=0x13, CVT_E0=0x14, CVT_E1=0x15,
+               BS_M=0x16, BS_E0=0x17, BS_E1=0x18, BS_A=0x19)
 
     def __init__(self, n, qs, t, eta, frac_bits, max_group, seed, psi_t):
         self.n, self.qs, self.t, self.eta = n, list(qs), t, eta
@@ -204,3 +205,26 @@ class PyBFV:
         c0 = [(ct[0][k] + sum(h[0][k] for h in shares)) % self.Q for k in range(self.n)]
         c1 = [sum(h[1][k] for h in shares) % self.Q for k in range(self.n)]
         return c0, c1
+
+    # ---- MBFV.Bootstrap (Sec. 4.2 item 4): collective refresh ----
+    def bootstrap_alpha(self, group, cti):
+        limbs = [uniform(self.seed, self.DOM["BS_A"], i, 0, group, cti, q, self.n) for i, q in enumerate(self.qs)]
+        return [crt([limbs[i][k] for i in range(len(self.qs))], self.qs) for k in range(self.n)]
+
+    def bootstrap_share(self, s_k, ct, party, group, cti):
+        """Eq. (3): (eta0, eta1) = (s_k c1 - Lambda M_k + e0_k, -s_k alpha + Lambda M_k + e1_k)."""
+        M = uniform(self.seed, self.DOM["BS_M"], 0, party, group, cti, self.t, self.n)
+        e0 = cbd(self.seed, self.DOM["BS_E0"], party, group, cti, self.eta, self.n)
+        e1 = cbd(self.seed, self.DOM["BS_E1"], party, group, cti, self.eta, self.n)
+        alpha = self.bootstrap_alpha(group, cti)
+        sc1 = negacyclic(ct[1], s_k, self.Q)
+        sa = negacyclic(alpha, s_k, self.Q)
+        eta0 = [(sc1[k] - self.Lam * M[k] + e0[k]) % self.Q for k in range(self.n)]
+        eta1 = [(-sa[k] + self.Lam * M[k] + e1[k]) % self.Q for k in range(self.n)]
+        return (eta0, eta1), (M, e0, e1)
+
+    def bootstrap_combine(self, ct, shares, group, cti):
+        y = [(ct[0][k] + sum(h[0][k] for h in shares)) % self.Q for k in range(self.n)]
+        x = self.scale_round(y)
+        c0 = [(self.Lam * x[k] + sum(h[1][k] for h in shares)) % self.Q for k in range(self.n)]
+        return (c0, self.bootstrap_alpha(group, cti)), x

@@ -392,6 +392,72 @@ def test_convert_noise_identity(orc):
     assert ref.decrypt(rs, new_ct) == m
 
 
+@pytest.mark.parametrize("log2n,bits,L,t,K", [(3, 30, 2, 17, 3), (4, 36, 3, 97, 4), (4, 60, 4, 65537, 2), (3, 30, 1, 17, 1)])
+def test_bootstrap_equals_bruteforce_big_integer_bfv(orc, log2n, bits, L, t, K):
+    """MBFV.Bootstrap (Sec. 4.2 item 4): alpha, every share (Eq. (3)) and the refreshed ciphertext
+    against the big-integer reference; the refreshed ciphertext decrypts to the same plaintext."""
+    o, ref, qs = _toy(orc, log2n, bits, L, t, K, 3)
+    n = 1 << log2n
+    rng = np.random.default_rng(log2n * 77 + L)
+    group, cti = 6, 11
+    keys = [ref.keygen(k) for k in range(K)]
+    p0 = ref.aggregate_pk([k[2] for k in keys])
+    okeys = [o.keygen_share(k) for k in range(K)]
+    opk = o.aggregate_pk([k[1] for k in okeys])
+    ms = [[int(v) for v in rng.integers(0, t, n)] for _ in range(K)]
+    cts = [ref.encrypt(p0, ms[k], k, group, cti)[0] for k in range(K)]
+    octs = [o.encrypt(opk, np.array([ms[k]], dtype=np.uint64), k, group, ct_base=cti) for k in range(K)]
+    agg, oagg = cts[0], octs[0]
+    for k in range(1, K):
+        agg = ref.add(agg, cts[k])
+        oagg = o.add(oagg, octs[k])
+    assert np.array_equal(o.bootstrap_alpha(group, cti), _residues(ref.bootstrap_alpha(group, cti), qs))
+    shares = [ref.bootstrap_share(keys[k][0], agg, k, group, cti)[0] for k in range(K)]
+    oshares = [o.bootstrap_share(okeys[k][0], oagg, k, group, ct_base=cti) for k in range(K)]
+    for k in range(K):
+        assert np.array_equal(oshares[k][0, 0], _residues(shares[k][0], qs))
+        assert np.array_equal(oshares[k][0, 1], _residues(shares[k][1], qs))
+    new_ct, _ = ref.bootstrap_combine(agg, shares, group, cti)
+    onew = o.bootstrap_combine(oagg, oshares, group, ct_base=cti)
+    assert np.array_equal(onew[0, 0], _residues(new_ct[0], qs)) and np.array_equal(onew[0, 1], _residues(new_ct[1], qs))
+    expect = [sum(m[j] for m in ms) % t for j in range(n)]
+    s_sum = [sum(k[0][j] for k in keys) for j in range(n)]
+    assert ref.decrypt(s_sum, new_ct) == expect
+    assert [int(v) for v in o.decrypt_with_secret(_residues(s_sum, qs), onew)[0]] == expect
+    # the refreshed ciphertext goes through the collective decryption like any other
+    plain_shares = [o.partial_decrypt(okeys[k][0], onew, k, group, ct_base=cti) for k in range(K)]
+    assert [int(v) for v in o.combine(onew, plain_shares)[0]] == expect
+
+
+def test_bootstrap_noise_is_reset(orc):
+    """Eq. (3) expanded: with M = sum M_k as an integer polynomial and x = (m - M) mod t,
+    c0' + s c1' - Lambda m = e1 + j (Q mod t), j = (m - M - x) / t coefficient-wise: the noise of
+    the input ciphertext is gone, only e1 = sum e1_k and the wrap term remain."""
+    o, ref, qs = _toy(orc, 5, 36, 2, 193, 3, 2)
+    n, K, group, cti = 32, 3, 2, 5
+    t = 193
+    keys = [ref.keygen(k) for k in range(K)]
+    p0 = ref.aggregate_pk([k[2] for k in keys])
+    s = [sum(k[0][j] for k in keys) for j in range(n)]
+    m = [(5 * j + 1) % t for j in range(n)]
+    ct = ref.encrypt(p0, m, 0, group, cti)[0]
+    for _ in range(3):                       # add the ciphertext to itself: more input noise
+        ct = ref.add(ct, ref.encrypt(p0, [0] * n, 1, group, cti)[0])
+    e_in = ref.noise(s, ct, m)
+    parts = [ref.bootstrap_share(keys[k][0], ct, k, group, cti) for k in range(K)]
+    new_ct, x = ref.bootstrap_combine(ct, [p[0] for p in parts], group, cti)
+    M = [sum(p[1][0][j] for p in parts) for j in range(n)]
+    e1 = [sum(p[1][2][j] for p in parts) for j in range(n)]
+    assert x == [(m[j] - M[j]) % t for j in range(n)]
+    jwrap = [(m[j] - M[j] - x[j]) // t for j in range(n)]
+    assert all((m[j] - M[j] - x[j]) % t == 0 for j in range(n))
+    r_t = ref.Q % t
+    noise = ref.noise(s, new_ct, m)
+    assert noise == [e1[j] + jwrap[j] * r_t for j in range(n)]
+    assert max(abs(v) for v in e_in) > max(abs(v) for v in e1)          # the input was noisier
+    assert ref.decrypt(s, new_ct) == m
+
+
 def test_noise_identity_and_margin(orc):
     """c0 + c1 s - Lambda m = -mu e_pk + e0 + e1 s exactly (Sec. 3.2 item 3 expanded), and it
     stays below Q/(2t) minus the wrap term (correctness condition under Eq. (2))."""
