@@ -225,6 +225,27 @@ d2mhe_status d2mhe_round_convert(d2mhe_ctx *ctx, const d2mhe_round_desc *desc,
                                  const d2mhe_convert_desc *conv, void *scratch, size_t scratch_bytes,
                                  void *const *phase_events, void *stream);
 
+/* ---- MBFV.Bootstrap: collective refresh of a ciphertext (Sec. 4.2 item 4, Eq. (3)) ------------- */
+/* The members of a group turn a ciphertext ct = (c0, c1) under their collective key into a
+ * fresh-like one (noise sum_k e1_k) of the same plaintext, without anybody learning it:
+ * every member masks its decryption share with a random M_k in R_t.
+ *
+ * The common random polynomial alpha of ciphertext indices ct_base .. ct_base + C - 1 of a group,
+ * uniform in R_q, evaluation form, alpha [C][L][N].                                         */
+d2mhe_status d2mhe_bootstrap_alpha(d2mhe_ctx *ctx, uint32_t group, uint32_t ct_base, uint32_t C,
+                                   uint64_t *alpha, void *stream);
+/* Member `party`'s share, Eq. (3):
+ *   (eta0, eta1) = (s_k c1 - Lambda M_k + e0_k, -s_k alpha + Lambda M_k + e1_k),  share [C][2][L][N],
+ * M_k uniform in R_t, e0_k, e1_k from chi, randomness indexed by (party, group, ct_base + c).   */
+d2mhe_status d2mhe_bootstrap_share(d2mhe_ctx *ctx, const uint64_t *sk_share, const uint64_t *ct,
+                                   const uint64_t *alpha, uint32_t C, uint32_t party, uint32_t group,
+                                   uint32_t ct_base, uint64_t *share, void *stream);
+/* ct' = ([round(t/Q [c0 + sum_k eta0_k]_Q)]_t Lambda + sum_k eta1_k, alpha), ct_out [C][2][L][N]
+ * (may not alias ct).  shares: HOST array of K device pointers.  Rounding as in d2mhe_combine. */
+d2mhe_status d2mhe_bootstrap_combine(d2mhe_ctx *ctx, const uint64_t *ct, const uint64_t *alpha,
+                                     const uint64_t *const *shares, uint32_t K, uint32_t C,
+                                     uint64_t *ct_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

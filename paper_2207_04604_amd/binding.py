@@ -24,6 +24,7 @@ SYMBOLS = [
     "d2mhe_round", "d2mhe_round_group",
     "d2mhe_receiver_keygen", "d2mhe_convert_share", "d2mhe_convert_combine", "d2mhe_decrypt",
     "d2mhe_round_convert_scratch_bytes", "d2mhe_round_convert",
+    "d2mhe_bootstrap_alpha", "d2mhe_bootstrap_share", "d2mhe_bootstrap_combine",
 ]
 
 
@@ -94,6 +95,9 @@ def lib():
         "d2mhe_decrypt": (i32, [vp, vp, vp, u32, vp, vp]),
         "d2mhe_round_convert_scratch_bytes": (sz, [vp, u32, u32, u32, u64]),
         "d2mhe_round_convert": (i32, [vp, C.POINTER(RoundDesc), C.POINTER(ConvertDesc), vp, sz, vp, vp]),
+        "d2mhe_bootstrap_alpha": (i32, [vp, u32, u32, u32, vp, vp]),
+        "d2mhe_bootstrap_share": (i32, [vp, vp, vp, vp, u32, u32, u32, u32, vp, vp]),
+        "d2mhe_bootstrap_combine": (i32, [vp, vp, vp, vp, u32, u32, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -296,6 +300,18 @@ class Context:
         ev = (C.c_void_p * 5)(*phase_events) if phase_events is not None else None
         _check(lib().d2mhe_round_convert(self._h, C.byref(desc), C.byref(conv), _ptr(scratch), scratch_bytes, ev,
                                          stream), "d2mhe_round_convert")
+
+    # ---- MBFV.Bootstrap ----
+    def bootstrap_alpha(self, group, ct_base, C_, alpha, stream=None):
+        _check(lib().d2mhe_bootstrap_alpha(self._h, group, ct_base, C_, _ptr(alpha), stream), "d2mhe_bootstrap_alpha")
+
+    def bootstrap_share(self, sk_share, ct, alpha, C_, party, group, ct_base, share, stream=None):
+        _check(lib().d2mhe_bootstrap_share(self._h, _ptr(sk_share), _ptr(ct), _ptr(alpha), C_, party, group, ct_base,
+                                           _ptr(share), stream), "d2mhe_bootstrap_share")
+
+    def bootstrap_combine(self, ct, alpha, shares, C_, ct_out, stream=None):
+        _check(lib().d2mhe_bootstrap_combine(self._h, _ptr(ct), _ptr(alpha), _ptr_table(shares), len(shares), C_,
+                                             _ptr(ct_out), stream), "d2mhe_bootstrap_combine")
 
     def round_group(self, pk, sk_shares, grads, members, group, n_values, out_sum, scratch, scratch_bytes,
                     stream=None):

@@ -62,6 +62,13 @@ struct EngineOps {
                                     const uint64_t *sk, bool keep_c1, uint32_t C, uint64_t *pt, hipStream_t);
     d2mhe_status (*convert_combine_decode)(d2mhe_ctx *, const RecvJobs &jobs, uint32_t njobs, size_t stride,
                                            uint32_t C, uint64_t n_values, hipStream_t);
+    // MBFV.Bootstrap
+    d2mhe_status (*bootstrap_alpha)(d2mhe_ctx *, uint32_t group, uint32_t ct_base, uint32_t C, uint64_t *alpha,
+                                    hipStream_t);
+    d2mhe_status (*bootstrap_share)(d2mhe_ctx *, const ConvJobs &jobs, uint32_t njobs, uint32_t ct_base, uint32_t C,
+                                    hipStream_t);
+    d2mhe_status (*bootstrap_combine)(d2mhe_ctx *, const uint64_t *ct, const PtrList &shares, uint32_t K,
+                                      const uint64_t *alpha, uint32_t C, uint64_t *ct_out, hipStream_t);
 };
 
 const EngineOps *ops_f_10();

@@ -564,6 +564,56 @@ d2mhe_status d2mhe_decrypt(d2mhe_ctx *ctx, const uint64_t *sk, const uint64_t *c
     return engine_ops(ctx)->convert_combine(ctx, ct, none, 0, sk, true, C, pt, (hipStream_t)stream);
 }
 
+// ---- MBFV.Bootstrap ----------------------------------------------------------------------------
+
+d2mhe_status d2mhe_bootstrap_alpha(d2mhe_ctx *ctx, uint32_t group, uint32_t ct_base, uint32_t C, uint64_t *alpha,
+                                   void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!alpha) return D2MHE_ERR_NULL;
+    if (misaligned(alpha)) return D2MHE_ERR_ALIGN;
+    if (group > 0xffffu || (uint64_t)ct_base + C > 0xffffffffull || C > 0xffffu * 0x10000ull) return D2MHE_ERR_RANGE;
+    if (C == 0) return D2MHE_OK;
+    return engine_ops(ctx)->bootstrap_alpha(ctx, group, ct_base, C, alpha, (hipStream_t)stream);
+}
+
+d2mhe_status d2mhe_bootstrap_share(d2mhe_ctx *ctx, const uint64_t *sk_share, const uint64_t *ct,
+                                   const uint64_t *alpha, uint32_t C, uint32_t party, uint32_t group,
+                                   uint32_t ct_base, uint64_t *share, void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!sk_share || !ct || !alpha || !share) return D2MHE_ERR_NULL;
+    if (misaligned(sk_share) || misaligned(ct) || misaligned(alpha) || misaligned(share)) return D2MHE_ERR_ALIGN;
+    if (party > 0xffffu || group > 0xffffu || (uint64_t)ct_base + C > 0xffffffffull) return D2MHE_ERR_RANGE;
+    if (C == 0) return D2MHE_OK;
+    ConvJobs jobs;
+    jobs.sk[0] = sk_share;
+    jobs.pk[0] = alpha;
+    jobs.ct[0] = ct;
+    jobs.out[0] = share;
+    jobs.who[0] = party;
+    jobs.group[0] = group;
+    return engine_ops(ctx)->bootstrap_share(ctx, jobs, 1, ct_base, C, (hipStream_t)stream);
+}
+
+d2mhe_status d2mhe_bootstrap_combine(d2mhe_ctx *ctx, const uint64_t *ct, const uint64_t *alpha,
+                                     const uint64_t *const *shares, uint32_t K, uint32_t C, uint64_t *ct_out,
+                                     void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!ct || !alpha || !shares || !ct_out) return D2MHE_ERR_NULL;
+    if (K == 0 || K > (uint32_t)MAX_GROUP || K > ctx->max_group) return D2MHE_ERR_RANGE;
+    if (misaligned(ct) || misaligned(alpha) || misaligned(ct_out)) return D2MHE_ERR_ALIGN;
+    PtrList sh;
+    for (uint32_t k = 0; k < K; ++k) {
+        if (!shares[k]) return D2MHE_ERR_NULL;
+        if (misaligned(shares[k])) return D2MHE_ERR_ALIGN;
+        sh.p[k] = shares[k];
+    }
+    if (C == 0) return D2MHE_OK;
+    return engine_ops(ctx)->bootstrap_combine(ctx, ct, sh, K, alpha, C, ct_out, (hipStream_t)stream);
+}
+
 namespace {
 
 // words of scratch for J (party, group) jobs, G groups, C ciphertext indices; S conversion shares

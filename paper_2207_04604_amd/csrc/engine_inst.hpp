@@ -139,18 +139,45 @@ struct Launch {
         return D2MHE_OK;
     }
 
+    static d2mhe_status bootstrap_alpha(d2mhe_ctx *ctx, uint32_t group, uint32_t ct_base, uint32_t C, uint64_t *alpha,
+                                        hipStream_t st)
+    {
+        hipLaunchKernelGGL(k_bootstrap_alpha<ENG>, dim3(C, ctx->L), dim3(ENG::T), 0, st, alpha, group, ct_base,
+                           ctx->d_tabs, ctx->rc);
+        D2_LAUNCHED(ctx);
+        return D2MHE_OK;
+    }
+
+    static d2mhe_status bootstrap_share(d2mhe_ctx *ctx, const ConvJobs &jobs, uint32_t njobs, uint32_t ct_base,
+                                        uint32_t C, hipStream_t st)
+    {
+        hipLaunchKernelGGL(k_bootstrap_share<ENG>, dim3(C, njobs), dim3(ENG::T), 0, st, jobs, ct_base, ctx->d_tabs,
+                           ctx->rc);
+        D2_LAUNCHED(ctx);
+        return D2MHE_OK;
+    }
+
+    static d2mhe_status bootstrap_combine(d2mhe_ctx *ctx, const uint64_t *ct, const PtrList &shares, uint32_t K,
+                                          const uint64_t *alpha, uint32_t C, uint64_t *ct_out, hipStream_t st)
+    {
+        hipLaunchKernelGGL(k_bootstrap_combine<ENG>, dim3(C), dim3(ENG::T), 0, st, ct, shares, K, alpha, ct_out,
+                           ctx->d_tabs, ctx->rc);
+        D2_LAUNCHED(ctx);
+        return D2MHE_OK;
+    }
+
     // full set (ring degrees a single workgroup can hold)
     static EngineOps full()
     {
         return EngineOps{ENG::ELOG, ENG::LOGB, &ntt, &keygen, &encode, &decode, &encrypt, &share, &combine,
                          &combine_decode, &receiver_keygen, &convert_share, &convert_combine,
-                         &convert_combine_decode};
+                         &convert_combine_decode, &bootstrap_alpha, &bootstrap_share, &bootstrap_combine};
     }
     // transforms only (longer rings)
     static EngineOps transforms_only()
     {
         return EngineOps{ENG::ELOG, ENG::LOGB, &ntt,    nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
-                         nullptr,   nullptr,   nullptr, nullptr, nullptr};
+                         nullptr,   nullptr,   nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     }
 };
 

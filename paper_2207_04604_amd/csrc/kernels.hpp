@@ -636,22 +636,28 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_share(ShareJobs jobs, ui
 // parts exactly, fractional parts in 64-bit fixed point (each term is truncated by less
 // than 2^-63, so the rounding is exact unless t y / Q lies within L * 2^-63 of a half-integer).
 // SH(j) returns the share buffer of member j.
-// CONVERT (MBFV.Convert, Eq. (2)): a share is a pair (h0, h1) [C][2][L][N] and the receiver's
+// MODE 1 (MBFV.Convert, Eq. (2)): a share is a pair (h0, h1) [C][2][L][N] and the receiver's
 // single-key decryption is folded in: y = c0 + sum h0_k + (z0 + sum h1_k) sk, where z0 = c1 of
 // `ct` if keep_c1 (plain BFV.Decrypt of `ct` when K = 0) and 0 otherwise (the converted
-// ciphertext drops the old c1).  skr: the receiver's prepared secret key.
+// ciphertext drops the old c1).  aux: the receiver's prepared secret key.
+// MODE 2 (MBFV.Bootstrap, Eq. (3)): a share is a pair (eta0, eta1); y = c0 + sum eta0_k is rounded
+// to x in R_t, and the refreshed ciphertext (Lambda x + sum eta1_k, alpha) goes to ct_out.
+// aux: alpha [C][L][N] in evaluation form.
 // -------------------------------------------------------------------------------------
-template <class ENG, bool DECODE, bool CONVERT, class SH>
-D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_t K, const uint64_t *skr,
+enum { COMBINE_COLLECTIVE = 0, COMBINE_CONVERT = 1, COMBINE_BOOTSTRAP = 2 };
+template <class ENG, bool DECODE, int MODE, class SH>
+D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_t K, const uint64_t *aux,
                          bool keep_c1, uint64_t *pt, float *out, uint64_t n_values, const LimbTab *tabs,
                          const RoundConst &rc)
 {
+    constexpr bool CONVERT = MODE == COMBINE_CONVERT;
+    const uint64_t *skr = aux;
     typedef typename ENG::A A;
     constexpr int E = ENG::E;
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x, L = rc.L;
     const size_t LN = (size_t)L * ENG::NB;
-    const size_t share_ct = (CONVERT ? 2 : 1) * LN;       // words of one share per ciphertext index
+    const size_t share_ct = (MODE == COMBINE_COLLECTIVE ? 1 : 2) * LN;       // words of one share per ciphertext index
     const uint64_t *c0 = ct + (size_t)c * 2 * LN;
     uint64_t acc_int[E], acc_frac[E];
 #pragma unroll
@@ -745,7 +751,39 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
         r = r >= td ? r - td : r;
         m[k] = (uint32_t)r;
     }
-    if (DECODE) {
+    if constexpr (MODE == COMBINE_BOOTSTRAP) {
+        // x sits where a forward transform takes its input: c0' = NTT(Lambda x) + sum eta1_k, c1' = alpha
+        uint64_t *ct_out = pt + (size_t)c * 2 * LN;
+        const uint64_t *alpha = aux + (size_t)c * LN;
+        for (uint32_t limb = 0; limb < L; ++limb) {
+            const LimbTab tb = load_tab(tabs, limb);
+            const uint64_t q = tb.q;
+            const typename A::Mod md = A::mod(q, tb.one_s);
+            const typename A::Twid lam = A::tw(tb.lambda);
+            const size_t off = (size_t)limb * ENG::NB;
+            const int tl = opaque(tid);
+            typename A::elem x[E];
+#pragma unroll
+            for (int k = 0; k < E; ++k) x[k] = A::mul(A::from_canon((uint64_t)opaque(m[k]), md), lam, md);
+            ENG::forward(x, lds, tl, 0, tb.fwd, md);
+            uint64_t y[E], hv[E];
+#pragma unroll
+            for (int k = 0; k < E; ++k) y[k] = A::canon_fwd(x[k], md);
+            for (uint32_t j = 0; j < K; ++j) {
+                const uint64_t *h = share_of(j) + (size_t)c * share_ct + LN + off;
+#pragma unroll
+                for (int k = 0; k < E; ++k) hv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
+#pragma unroll
+                for (int k = 0; k < E; ++k) y[k] = add_mod(y[k], hv[k], q);
+            }
+#pragma unroll
+            for (int k = 0; k < E; ++k) {
+                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
+                st64(ct_out + off, lo, so, y[k]);
+                st64(ct_out + LN + off, lo, so, ld64(alpha + off, lo, so));
+            }
+        }
+    } else if (DECODE) {
         decode_from_regs<ENG>(m, lds, tid, out, (uint64_t)c * ENG::NB, n_values, load_tab(tabs, L), rc);
     } else {
 #pragma unroll
@@ -759,7 +797,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_combine(const uint64_t *
                                                     const LimbTab *tabs, RoundConst rc)
 {
     __shared__ uint64_t lds[ENG::LDS_WORDS];
-    combine_body<ENG, false, false>(lds, ct, [&](uint32_t j) { return (const uint64_t *)shares.p[j]; }, K,
+    combine_body<ENG, false, COMBINE_COLLECTIVE>(lds, ct, [&](uint32_t j) { return (const uint64_t *)shares.p[j]; }, K,
                                     (const uint64_t *)nullptr, false, pt, (float *)nullptr, 0, tabs, rc);
 }
 
@@ -771,7 +809,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_combine_decode(GroupJobs
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const uint32_t job = blockIdx.y;
     const uint64_t *first = jobs.first[job];
-    combine_body<ENG, true, false>(lds, jobs.ct[job], [&](uint32_t j) { return first + (size_t)j * stride; },
+    combine_body<ENG, true, COMBINE_COLLECTIVE>(lds, jobs.ct[job], [&](uint32_t j) { return first + (size_t)j * stride; },
                                    jobs.K[job], (const uint64_t *)nullptr, false, (uint64_t *)nullptr,
                                    (float *)jobs.out[job], n_values, tabs, rc);
 }
@@ -937,7 +975,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_combine(const ui
                                                             const LimbTab *tabs, RoundConst rc)
 {
     __shared__ uint64_t lds[ENG::LDS_WORDS];
-    combine_body<ENG, false, true>(lds, ct, [&](uint32_t j) { return (const uint64_t *)shares.p[j]; }, K, skr,
+    combine_body<ENG, false, COMBINE_CONVERT>(lds, ct, [&](uint32_t j) { return (const uint64_t *)shares.p[j]; }, K, skr,
                                    keep_c1 != 0, pt, (float *)nullptr, 0, tabs, rc);
 }
 
@@ -950,9 +988,156 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_combine_decode(R
     __shared__ uint64_t lds[ENG::LDS_WORDS];
     const uint32_t job = blockIdx.y;
     const uint64_t *first = jobs.first[job];
-    combine_body<ENG, true, true>(lds, jobs.ct[job], [&](uint32_t j) { return first + (size_t)j * stride; },
+    combine_body<ENG, true, COMBINE_CONVERT>(lds, jobs.ct[job], [&](uint32_t j) { return first + (size_t)j * stride; },
                                   jobs.K[job], jobs.sk[job], false, (uint64_t *)nullptr, (float *)jobs.out[job],
                                   n_values, tabs, rc);
+}
+
+// -------------------------------------------------------------------------------------
+// MBFV.Bootstrap (Sec. 4.2 item 4): collective refresh of a ciphertext.
+// -------------------------------------------------------------------------------------
+// The 128-bit little-endian value of a block reduced mod q by Horner over its four words, with
+// 2^32 mod q as a prepared multiplicand (c32, quotient c32s) and floor(2^64 / q) for the words.
+struct UniformMod {
+    uint64_t q, c32, c32s, one64;
+};
+D2_DEV UniformMod uniform_mod_setup(uint64_t q)
+{
+    UniformMod u;
+    u.q = q;
+    u.c32 = (1ull << 32) % q;
+    u.c32s = shoup_quotient(u.c32, q);
+    u.one64 = q > 1 ? shoup_quotient(1, q) : 0;
+    return u;
+}
+D2_DEV uint64_t uniform_mod_fast(const Block4 &b, const UniformMod &u)
+{
+    uint64_t r = mul_shoup64(b.w[3], 1, u.one64, u.q);
+#pragma unroll
+    for (int i = 2; i >= 0; --i)
+        r = add_mod(mul_shoup64(r, u.c32, u.c32s, u.q), mul_shoup64(b.w[i], 1, u.one64, u.q), u.q);
+    return r;
+}
+
+// alpha of ciphertext indices ct_base .. ct_base + C - 1 of a group, evaluation form, [C][L][N].
+// grid = (C, L).  Coefficient n of limb i = block n of (BS_A, limb i, group) reduced mod q_i.
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_bootstrap_alpha(uint64_t *alpha, uint32_t group, uint32_t ct_base,
+                                                            const LimbTab *tabs, RoundConst rc)
+{
+    typedef typename ENG::A A;
+    constexpr int E = ENG::E;
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x, limb = blockIdx.y, L = rc.L;
+    const LimbTab tb = load_tab(tabs, limb);
+    const typename A::Mod md = A::mod(tb.q, tb.one_s);
+    const UniformMod um = uniform_mod_setup(tb.q);
+    typename A::elem x[E];
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+        const uint32_t n = (uint32_t)ENG::coef_pos(k, tid);
+        x[k] = A::from_canon(uniform_mod_fast(philox4x32_10(n, ct_base + c, 0, counter_tag(DOM_BS_A, limb, group), rc.key), um), md);
+    }
+    ENG::forward(x, lds, tid, 0, tb.fwd, md);
+    uint64_t *o = alpha + ((size_t)c * L + limb) * ENG::NB;
+#pragma unroll
+    for (int k = 0; k < E; ++k) st64(o, 8u * (uint32_t)tid, 8u * ENG::T * k, A::canon_fwd(x[k], md));
+}
+
+// A member's refresh share, Eq. (3), in evaluation form.  grid = (C, jobs); jobs.pk holds alpha.
+//   eta0 = s_k c1 + NTT(e0 - Lambda M),   eta1 = NTT(Lambda M + e1) - s_k alpha
+// M uniform mod t (one block per coefficient), e0, e1 from chi.
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_bootstrap_share(ConvJobs jobs, uint32_t ct_base, const LimbTab *tabs,
+                                                            RoundConst rc)
+{
+    typedef typename ENG::A A;
+    typedef typename A::elem elem;
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    uint32_t *lds32 = (uint32_t *)lds;
+    constexpr int E = ENG::E;
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x, job = blockIdx.y, L = rc.L;
+    const size_t LN = (size_t)L * ENG::NB;
+    const uint32_t party = jobs.who[job], group = jobs.group[job];
+    const uint64_t *sk = jobs.sk[job];
+    const uint64_t *alpha = jobs.pk[job] + (size_t)c * LN;
+    const uint64_t *c1 = jobs.ct[job] + ((size_t)c * 2 + 1) * LN;
+    uint64_t *out = jobs.out[job] + (size_t)c * 2 * LN;
+    // staging: words [0, NB) the masks, words [NB, 2 NB) e0 | e1 << 8 (two's complement bytes)
+    const UniformMod um = uniform_mod_setup(rc.t);
+    for (int n = tid; n < ENG::NB; n += ENG::T)
+        lds32[n] = (uint32_t)uniform_mod_fast(philox4x32_10(n, ct_base + c, party, counter_tag(DOM_BS_M, 0, group), rc.key), um);
+    for (int j = tid; j < ENG::NB / 2; j += ENG::T) {
+        int32_t e0[2], e1[2];
+        cbd2(philox4x32_10(j, ct_base + c, party, counter_tag(DOM_BS_E0, 0, group), rc.key), rc.eta_mask, e0);
+        cbd2(philox4x32_10(j, ct_base + c, party, counter_tag(DOM_BS_E1, 0, group), rc.key), rc.eta_mask, e1);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            lds32[ENG::NB + 2 * j + i] = ((uint32_t)e0[i] & 0xffu) | (((uint32_t)e1[i] & 0xffu) << 8);
+    }
+    __syncthreads();
+    uint32_t mv[E], ev[E];
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+        mv[k] = lds32[ENG::coef_pos(k, tid)];
+        ev[k] = lds32[ENG::NB + ENG::coef_pos(k, tid)];
+    }
+    for (uint32_t limb = 0; limb < L; ++limb) {
+        const LimbTab tb = load_tab(tabs, limb);
+        const uint64_t q = tb.q;
+        const typename A::Mod md = A::mod(q, tb.one_s);
+        const typename A::Twid lam = A::tw(tb.lambda);
+        const size_t off = (size_t)limb * ENG::NB;
+        const int tl = opaque(tid);
+        uint64_t lm[E];                                     // Lambda M mod q, canonical
+#pragma unroll
+        for (int k = 0; k < E; ++k) lm[k] = A::canon_acc(A::mul(A::from_canon((uint64_t)opaque(mv[k]), md), lam, md), md);
+        elem x[E];
+#pragma unroll
+        for (int k = 0; k < E; ++k)
+            x[k] = A::add(A::from_canon(lm[k] ? q - lm[k] : 0, md), A::from_small(sbyte(opaque(ev[k]), 0), md));
+        ENG::forward(x, lds, tl, 0, tb.fwd, md);
+        {
+            typename A::Twid kv[E];
+#pragma unroll
+            for (int k = 0; k < E; ++k) kv[k] = A::key(sk + off, sk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
+#pragma unroll
+            for (int k = 0; k < E; ++k) {
+                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
+                const uint64_t cv = ld64(c1 + off, lo, so);
+                st64(out + off, lo, so, A::canon_acc(A::add(A::mul(A::from_canon(cv, md), kv[k], md), x[k]), md));
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < E; ++k)
+            x[k] = A::add(A::from_canon(lm[k], md), A::from_small(sbyte(opaque(ev[k]), 1), md));
+        ENG::forward(x, lds, opaque(tl), 0, tb.fwd, md);
+        {
+            typename A::Twid kv[E];
+#pragma unroll
+            for (int k = 0; k < E; ++k) kv[k] = A::key(sk + off, sk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
+#pragma unroll
+            for (int k = 0; k < E; ++k) {
+                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
+                const uint64_t av = ld64(alpha + off, lo, so);
+                const uint64_t prod = A::canon_acc(A::mul(A::from_canon(av, md), kv[k], md), md);   // s_k alpha
+                st64(out + LN + off, lo, so, A::canon_acc(A::add(x[k], A::from_canon(prod ? q - prod : 0, md)), md));
+            }
+        }
+    }
+}
+
+// The receiver's side of MBFV.Bootstrap; grid = C.  ct_out [C][2][L][N].
+template <class ENG>
+__global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_bootstrap_combine(const uint64_t *ct, PtrList shares, uint32_t K,
+                                                              const uint64_t *alpha, uint64_t *ct_out,
+                                                              const LimbTab *tabs, RoundConst rc)
+{
+    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    combine_body<ENG, false, COMBINE_BOOTSTRAP>(lds, ct, [&](uint32_t j) { return (const uint64_t *)shares.p[j]; }, K,
+                                                alpha, false, ct_out, (float *)nullptr, 0, tabs, rc);
 }
 
 }  // namespace d2

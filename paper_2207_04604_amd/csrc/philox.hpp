@@ -17,7 +17,9 @@ enum : uint32_t {
     DOM_DEC_E = 7, DOM_BENCH = 8,
     // MBFV.Convert: a receiver's own key pair and the randomness of a conversion share (mu, e0, e1
     // consecutive, like the three domains of Encrypt)
-    DOM_RSK = 0x10, DOM_RPK_A = 0x11, DOM_RPK_E = 0x12, DOM_CVT_U = 0x13, DOM_CVT_E0 = 0x14, DOM_CVT_E1 = 0x15
+    DOM_RSK = 0x10, DOM_RPK_A = 0x11, DOM_RPK_E = 0x12, DOM_CVT_U = 0x13, DOM_CVT_E0 = 0x14, DOM_CVT_E1 = 0x15,
+    // MBFV.Bootstrap: mask M_k (uniform mod t), e0, e1 of a share, common polynomial alpha (per limb)
+    DOM_BS_M = 0x16, DOM_BS_E0 = 0x17, DOM_BS_E1 = 0x18, DOM_BS_A = 0x19
 };
 
 struct PhiloxKey { uint32_t k0, k1; };

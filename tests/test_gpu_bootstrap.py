@@ -1,0 +1,111 @@
+"""GPU parity of MBFV.Bootstrap (Sec. 4.2 item 4, Eq. (3)) through the C ABI: the common polynomial,
+every refresh share and the refreshed ciphertext bit-exact against the oracle; the refreshed
+ciphertext then goes through the ordinary collective decryption."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2207_04604_amd import binding as B
+from paper_2207_04604_amd.synth import CONFIGS
+
+from gpu_util import DEV, Keys, dzeros, make_pair, to_dev, to_eval, to_host
+from test_gpu_parity import fixed_point_sum
+
+pytestmark = pytest.mark.gpu
+
+
+def refresh_and_compare(cfg, o, ctx, perm, keys, members, group, grads, ct_base=0, extra_adds=0):
+    L, N = o.L, o.N
+    n_values = grads[members[0]].size
+    C_ = (n_values + N - 1) // N
+    opk, dpk = keys.group_pk(members, perm, check=False)
+    dagg, oagg = None, None
+    for k in members:
+        dpt = dzeros(C_ * N)
+        ctx.encode(to_dev(grads[k]), n_values, dpt, C_)
+        dct = dzeros(C_ * 2 * L * N)
+        ctx.encrypt(dpk, dpt, C_, k, group, ct_base, dct)
+        oct_ = o.encrypt(opk, o.encode(grads[k]), k, group, ct_base)
+        if dagg is None:
+            dagg, oagg = dct, oct_
+        else:
+            ctx.add(dagg, dct, C_)
+            oagg = o.add(oagg, oct_)
+    dalpha = dzeros(C_ * L * N)
+    ctx.bootstrap_alpha(group, ct_base, C_, dalpha)
+    oalpha = np.stack([o.bootstrap_alpha(group, (ct_base + c) & 0xffffffff) for c in range(C_)])
+    assert np.array_equal(to_host(dalpha, oalpha.shape), to_eval(o, perm, oalpha)), "alpha"
+    dshares, oshares = [], []
+    for k in members:
+        dsh = dzeros(C_ * 2 * L * N)
+        ctx.bootstrap_share(keys.sk[k], dagg, dalpha, C_, k, group, ct_base, dsh)
+        osh = o.bootstrap_share(keys.osk[k], oagg, k, group, ct_base)
+        assert np.array_equal(to_host(dsh, osh.shape), to_eval(o, perm, osh)), f"refresh share of party {k}"
+        dshares.append(dsh)
+        oshares.append(osh)
+    dnew = dzeros(C_ * 2 * L * N)
+    ctx.bootstrap_combine(dagg, dalpha, dshares, C_, dnew)
+    onew = o.bootstrap_combine(oagg, oshares, group, ct_base)
+    assert np.array_equal(to_host(dnew, onew.shape), to_eval(o, perm, onew)), "refreshed ciphertext"
+    # the refreshed ciphertext decrypts collectively to the same fixed-point sum
+    pshares = []
+    for k in members:
+        dsh = dzeros(C_ * L * N)
+        ctx.partial_decrypt(keys.sk[k], dnew, C_, k, group, ct_base, dsh)
+        pshares.append(dsh)
+    dout = dzeros(C_ * N)
+    ctx.combine(dnew, pshares, C_, dout)
+    dres = torch.zeros(n_values, dtype=torch.float32, device=DEV)
+    ctx.decode(dout, C_, n_values, dres)
+    expect = fixed_point_sum([grads[k] for k in members], cfg.frac_bits, o.encode_clamp())
+    assert np.array_equal(dres.cpu().numpy(), expect), "decoded sum after the refresh"
+
+
+def test_bootstrap_C1_every_coefficient():
+    cfg = CONFIGS["C1"]
+    o, ctx, perm = make_pair(cfg)
+    grads = cfg.gradients()
+    keys = Keys(o, ctx, perm, range(cfg.parties), check=False)
+    refresh_and_compare(cfg, o, ctx, perm, keys, cfg.groups()[0], 0, grads)
+    ctx.close()
+
+
+def test_bootstrap_C2_one_group_every_coefficient():
+    cfg = CONFIGS["C2"]
+    o, ctx, perm = make_pair(cfg)
+    grads = cfg.gradients()
+    keys = Keys(o, ctx, perm, range(cfg.parties), check=False)
+    refresh_and_compare(cfg, o, ctx, perm, keys, cfg.groups()[9], 9, grads)
+    ctx.close()
+
+
+def test_bootstrap_wide_primes_ragged_tail_and_extreme_ids():
+    from oracle import oracle as O
+    from paper_2207_04604_amd.synth import toy_config
+    for bits, log2n, L in ((54, 11, 2), (60, 10, 2), (36, 13, 2)):
+        cfg = toy_config(log2n, O.find_primes(bits, log2n, L), 65537, 3, (1 << log2n) + 77, frac_bits=6)
+        o, ctx, perm = make_pair(cfg)
+        rng = np.random.default_rng(bits + 1)
+        members = [0, 40000, 65535]
+        grads = {k: rng.normal(0, 3.0, cfg.n_values).astype(np.float32) for k in members}
+        keys = Keys(o, ctx, perm, members, check=False)
+        refresh_and_compare(cfg, o, ctx, perm, keys, members, 65535, grads, ct_base=2**32 - 4)
+        ctx.close()
+
+
+def test_bootstrap_argument_checks():
+    cfg = CONFIGS["C1"]
+    o, ctx, perm = make_pair(cfg)
+    L, N = o.L, o.N
+    buf = dzeros(4 * L * N)
+    with pytest.raises(B.D2mheError) as ei:
+        ctx.bootstrap_alpha(70000, 0, 1, buf)
+    assert ei.value.status == B.ERR_RANGE
+    with pytest.raises(B.D2mheError) as ei:
+        ctx.bootstrap_share(buf, buf, None, 1, 0, 0, 0, buf)
+    assert ei.value.status == B.ERR_NULL
+    with pytest.raises(B.D2mheError) as ei:
+        ctx.bootstrap_combine(buf, buf, [], 1, buf)
+    assert ei.value.status == B.ERR_RANGE
+    ctx.bootstrap_alpha(0, 0, 0, buf)        # C = 0: nothing to do
+    ctx.close()
