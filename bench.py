@@ -5,10 +5,11 @@ A step is one whole round of the hot path (encode + encrypt, homomorphic sum, de
 shares, combine + decode) for every group of the workload, with the float32 gradients and
 all keys already resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu] [--no-ntt] [--no-convert]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu] [--no-ntt] [--no-convert] [--no-bootstrap]
 
 Beside the headline round it reports the same round with the paper's own decryption path
-(key switching of every aggregate to its receivers, MBFV.Convert), the batched transform
+(key switching of every aggregate to its receivers, MBFV.Convert), a collective refresh of the
+aggregates (MBFV.Bootstrap), the batched transform
 micro-benchmark, and the CPU oracle timed on a bounded sample.
 """
 import argparse
@@ -48,6 +49,7 @@ def main():
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-ntt", action="store_true", help="skip the transform micro-benchmark")
+    ap.add_argument("--no-bootstrap", action="store_true", help="skip the collective refresh (MBFV.Bootstrap)")
     ap.add_argument("--no-convert", action="store_true",
                     help="skip the round with key switching to the receivers (MBFV.Convert)")
     ap.add_argument("--ntt-reps", type=int, default=20)
@@ -183,6 +185,50 @@ def main():
                      "hbm_algorithmic_GB_per_s": enc_bytes / 1e9 / (enc_ms * 1e-3),
                      "hbm_frac": enc_bytes / 1e9 / (enc_ms * 1e-3) / HBM_PEAK_GBS},
     }
+
+    # ---- MBFV.Bootstrap: the members of group 0 refresh all G*C aggregates the round left in the
+    # scratch (same work for each; the first C are group 0's own and are checked after the refresh)
+    if not args.no_bootstrap:
+        LN = L * N
+        nct = G * C_
+        agg = scratch[J * C_ * 2 * LN:(J + G) * C_ * 2 * LN]
+        g0 = groups[0]
+        alpha = dz(nct * LN)
+        bshares = [dz(nct * 2 * LN) for _ in g0]
+        fresh_ct = dz(nct * 2 * LN)
+
+        def refresh():
+            ctx.bootstrap_alpha(0, 0, nct, alpha, sptr)
+            for k, sh in zip(g0, bshares):
+                ctx.bootstrap_share(sks[k], agg, alpha, nct, k, 0, 0, sh, sptr)
+            ctx.bootstrap_combine(agg, alpha, bshares, nct, fresh_ct, sptr)
+
+        refresh()
+        torch.cuda.synchronize()
+        bsteps = max(1, min(args.steps, 10))
+        be = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        be[0].record(stream)
+        for _ in range(bsteps):
+            refresh()
+        be[1].record(stream)
+        torch.cuda.synchronize()
+        bms = be[0].elapsed_time(be[1]) / bsteps
+        # the refreshed aggregates of group 0 decrypt to the same sums
+        psh = [dz(C_ * LN) for _ in g0]
+        for k, sh in zip(g0, psh):
+            ctx.partial_decrypt(sks[k], fresh_ct, C_, k, 0, 0, sh, sptr)
+        bpt = dz(C_ * N)
+        ctx.combine(fresh_ct, psh, C_, bpt, sptr)
+        bout = torch.zeros(cfg.n_values, dtype=torch.float32, device=dev)
+        ctx.decode(bpt, C_, cfg.n_values, bout, sptr)
+        torch.cuda.synchronize()
+        if not torch.equal(bout, outs[0]):
+            print("bench.py: refreshed ciphertexts decrypt to something else", file=sys.stderr)
+            sys.exit(7)
+        result["bootstrap"] = {"what": f"collective refresh (Eq. (3)) of {nct} ciphertexts by {len(g0)} members: "
+                                       "common polynomial, one share per member, refreshed ciphertext",
+                               "ms": bms, "refreshed_ct_per_s": nct / (bms * 1e-3)}
+        del alpha, bshares, fresh_ct, psh
 
     # ---- the same round with MBFV.Convert: every node receives the sum of its closed neighbourhood
     # under its own key (three transforms per limb and share instead of one, two polynomials per share)
