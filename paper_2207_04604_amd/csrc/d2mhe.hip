@@ -255,6 +255,8 @@ d2mhe_status d2mhe_create(const d2mhe_params *p, void *dev_workspace, size_t byt
         } else {
             tb.one_s = (uint64_t)(((u128)1 << 63) / m);
         }
+        tb.pow32 = h_tw((((uint64_t)1) << 32) % m, m);
+        tb.inv64 = (uint64_t)((((u128)1) << 64) / m);
         const uint64_t ninv = h_inv((uint64_t)N % m, m);
         tb.ninv = h_entry(ar, ninv, m);
         tb.wn = h_entry(ar, h_mul(pw[h_bitrev(1u, (int)log2n)], ninv, m), m);   // inverse twiddle 1 times N^-1

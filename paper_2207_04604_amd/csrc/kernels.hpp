@@ -23,6 +23,8 @@ struct LimbTab {
     Tw gamma;           // (Q/q)^-1 mod q, integer pair
     uint64_t theta_hi;  // floor(t * 2^128 / q), high and low words
     uint64_t theta_lo;
+    Tw pow32;           // 2^32 mod q, integer pair like gamma (reduction of 128-bit uniform blocks)
+    uint64_t inv64;     // floor(2^64 / q)
     const Tw *fwd;      // forward twiddles, N entries
     const Tw *inv;      // inverse twiddles, N entries
 };
@@ -41,8 +43,23 @@ D2_DEV LimbTab load_tab(const LimbTab *tabs, uint32_t i)
     r.gamma = Tw{const_ld64(e, offsetof(LimbTab, gamma)), const_ld64(e, offsetof(LimbTab, gamma) + 8)};
     r.theta_hi = const_ld64(e, offsetof(LimbTab, theta_hi));
     r.theta_lo = const_ld64(e, offsetof(LimbTab, theta_lo));
+    r.pow32 = Tw{const_ld64(e, offsetof(LimbTab, pow32)), const_ld64(e, offsetof(LimbTab, pow32) + 8)};
+    r.inv64 = const_ld64(e, offsetof(LimbTab, inv64));
     r.fwd = (const Tw *)const_ld64(e, offsetof(LimbTab, fwd));
     r.inv = (const Tw *)const_ld64(e, offsetof(LimbTab, inv));
+    return r;
+}
+
+// The 128-bit little-endian value of a Philox block reduced mod q (uniform sampling): Horner over
+// its four words, r <- r * 2^32 + w, with 2^32 mod q as a prepared multiplicand and floor(2^64 / q)
+// to reduce the words themselves (they can exceed a modulus below 2^32).
+D2_DEV uint64_t uniform_mod(const Block4 &b, const LimbTab &tb)
+{
+    const uint64_t q = tb.q;
+    uint64_t r = mul_shoup64(b.w[3], 1, tb.inv64, q);
+#pragma unroll
+    for (int i = 2; i >= 0; --i)
+        r = add_mod(mul_shoup64(r, tb.pow32.w, tb.pow32.ws, q), mul_shoup64(b.w[i], 1, tb.inv64, q), q);
     return r;
 }
 
@@ -857,7 +874,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_receiver_keygen(uint32_t
 #pragma unroll
     for (int k = 0; k < E; ++k) {
         const uint32_t n = (uint32_t)ENG::coef_pos(k, tid);
-        x[k] = A::from_canon(uniform_mod(philox4x32_10(n, 0, party, counter_tag(DOM_RPK_A, limb, 0), rc.key), q), md);
+        x[k] = A::from_canon(uniform_mod(philox4x32_10(n, 0, party, counter_tag(DOM_RPK_A, limb, 0), rc.key), tb), md);
     }
     ENG::forward(x, lds, tid, 0, tb.fwd, md);
 #pragma unroll
@@ -996,29 +1013,6 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_combine_decode(R
 // -------------------------------------------------------------------------------------
 // MBFV.Bootstrap (Sec. 4.2 item 4): collective refresh of a ciphertext.
 // -------------------------------------------------------------------------------------
-// The 128-bit little-endian value of a block reduced mod q by Horner over its four words, with
-// 2^32 mod q as a prepared multiplicand (c32, quotient c32s) and floor(2^64 / q) for the words.
-struct UniformMod {
-    uint64_t q, c32, c32s, one64;
-};
-D2_DEV UniformMod uniform_mod_setup(uint64_t q)
-{
-    UniformMod u;
-    u.q = q;
-    u.c32 = (1ull << 32) % q;
-    u.c32s = shoup_quotient(u.c32, q);
-    u.one64 = q > 1 ? shoup_quotient(1, q) : 0;
-    return u;
-}
-D2_DEV uint64_t uniform_mod_fast(const Block4 &b, const UniformMod &u)
-{
-    uint64_t r = mul_shoup64(b.w[3], 1, u.one64, u.q);
-#pragma unroll
-    for (int i = 2; i >= 0; --i)
-        r = add_mod(mul_shoup64(r, u.c32, u.c32s, u.q), mul_shoup64(b.w[i], 1, u.one64, u.q), u.q);
-    return r;
-}
-
 // alpha of ciphertext indices ct_base .. ct_base + C - 1 of a group, evaluation form, [C][L][N].
 // grid = (C, L).  Coefficient n of limb i = block n of (BS_A, limb i, group) reduced mod q_i.
 template <class ENG>
@@ -1032,12 +1026,11 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_bootstrap_alpha(uint64_t
     const uint32_t c = blockIdx.x, limb = blockIdx.y, L = rc.L;
     const LimbTab tb = load_tab(tabs, limb);
     const typename A::Mod md = A::mod(tb.q, tb.one_s);
-    const UniformMod um = uniform_mod_setup(tb.q);
     typename A::elem x[E];
 #pragma unroll
     for (int k = 0; k < E; ++k) {
         const uint32_t n = (uint32_t)ENG::coef_pos(k, tid);
-        x[k] = A::from_canon(uniform_mod_fast(philox4x32_10(n, ct_base + c, 0, counter_tag(DOM_BS_A, limb, group), rc.key), um), md);
+        x[k] = A::from_canon(uniform_mod(philox4x32_10(n, ct_base + c, 0, counter_tag(DOM_BS_A, limb, group), rc.key), tb), md);
     }
     ENG::forward(x, lds, tid, 0, tb.fwd, md);
     uint64_t *o = alpha + ((size_t)c * L + limb) * ENG::NB;
@@ -1066,9 +1059,9 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_bootstrap_share(ConvJobs
     const uint64_t *c1 = jobs.ct[job] + ((size_t)c * 2 + 1) * LN;
     uint64_t *out = jobs.out[job] + (size_t)c * 2 * LN;
     // staging: words [0, NB) the masks, words [NB, 2 NB) e0 | e1 << 8 (two's complement bytes)
-    const UniformMod um = uniform_mod_setup(rc.t);
+    const LimbTab tt = load_tab(tabs, L);                 // the entry of the plaintext modulus
     for (int n = tid; n < ENG::NB; n += ENG::T)
-        lds32[n] = (uint32_t)uniform_mod_fast(philox4x32_10(n, ct_base + c, party, counter_tag(DOM_BS_M, 0, group), rc.key), um);
+        lds32[n] = (uint32_t)uniform_mod(philox4x32_10(n, ct_base + c, party, counter_tag(DOM_BS_M, 0, group), rc.key), tt);
     for (int j = tid; j < ENG::NB / 2; j += ENG::T) {
         int32_t e0[2], e1[2];
         cbd2(philox4x32_10(j, ct_base + c, party, counter_tag(DOM_BS_E0, 0, group), rc.key), rc.eta_mask, e0);

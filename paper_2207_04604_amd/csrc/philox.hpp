@@ -66,30 +66,4 @@ D2_DEV void cbd2(const Block4 &b, uint32_t mask, int32_t out[2])
     out[1] = __popc(b.w[2] & mask) - __popc(b.w[3] & mask);
 }
 
-// The 128-bit little-endian value of a block reduced mod q (q < 2^61): Horner over the
-// four words with 64-bit remainders.
-D2_DEV uint64_t uniform_mod(const Block4 &b, uint64_t q)
-{
-    // r = ((w3 * 2^32 + w2) * 2^32 + w1) * 2^32 + w0 mod q, keeping r < q < 2^61
-    uint64_t r = 0;
-#pragma unroll
-    for (int i = 3; i >= 0; --i) {
-        // r * 2^32 + w mod q without overflow: shift in four 8-bit steps (r < 2^61 -> r<<3 fits... )
-        // do it as 32 single-bit doublings is wasteful; use two 16-bit steps with 128-bit-free reduction:
-        uint64_t hi = r;
-#pragma unroll
-        for (int s = 0; s < 16; ++s) {           // 16 x (2 bits): hi*4 < 2^63
-            hi <<= 2;
-            // hi < 4q: bring back under q
-            if (hi >= 2 * q) hi -= 2 * q;
-            if (hi >= q) hi -= q;
-        }
-        uint64_t w = b.w[i];
-        w %= q;                                  // no-op unless q < 2^32
-        r = hi + w;
-        if (r >= q) r -= q;
-    }
-    return r;
-}
-
 }  // namespace d2

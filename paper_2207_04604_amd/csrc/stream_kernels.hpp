@@ -17,7 +17,7 @@ __global__ void __launch_bounds__(256) k_uniform(uint64_t *out, const LimbTab *t
     size_t poly = i >> log2n;
     uint32_t limb = (uint32_t)(poly % L), b = (uint32_t)(poly / L);
     Block4 blk = philox4x32_10(n, b, 0, counter_tag(domain, limb, 0), key);
-    out[i] = uniform_mod(blk, tabs[limb].q);
+    out[i] = uniform_mod(blk, tabs[limb]);
 }
 
 // values [L][N] (canonical) -> prepared polynomial: copy + Shoup quotients.
