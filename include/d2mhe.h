@@ -152,6 +152,9 @@ typedef struct {
     const float *const *grads;       /* [P] gradient by party id, n_values floats each      */
     float *const *out_sums;          /* [G] result per group, n_values floats each          */
     uint64_t n_values;
+    uint32_t ct_base;                /* first ciphertext index of this round: the randomness of
+                                        ciphertext c is indexed by ct_base + c; a training loop
+                                        passes iteration * C so that no index is used twice  */
 } d2mhe_round_desc;
 
 /* Scratch bytes for a round with num_jobs (party, group) pairs in num_groups groups.      */
@@ -174,6 +177,15 @@ d2mhe_status d2mhe_round_group(d2mhe_ctx *ctx, const uint64_t *pk,
                                const uint32_t *members, uint32_t K, uint32_t group,
                                uint64_t n_values, float *out_sum, void *scratch,
                                size_t scratch_bytes, void *stream);
+
+/* ---- the float step of one training iteration (Alg. 2 lines 9-10) ---------------------------- */
+/* w[j] = sum[j] * (1/K) - gamma * grad[j] in float32, each operation rounded on its own:
+ * the average over a closed neighbourhood of K nodes from the decoded sum (the weights 1/K of the
+ * mixing matrix are not elements of Z_t, so they are applied after decryption), then the local
+ * gradient step.  Device pointers; grad may be NULL when gamma is 0; w may alias sum.
+ * A multi-iteration run alternates d2mhe_round (or d2mhe_round_convert) with this call.      */
+d2mhe_status d2mhe_average_update(const float *sum, uint32_t K, const float *grad, float gamma,
+                                  uint64_t n, float *w, void *stream);
 
 /* ---- MBFV.Convert: key switching to a receiver's own key (Sec. 4.2 item 3) ------------------- */
 /* In the paper's protocol node i does not take part in a collective decryption of the

@@ -845,6 +845,23 @@ void orc_bootstrap_combine(const orc_ctx *c, const uint64_t *ct, const uint64_t 
     }
 }
 
+/* Alg. 2 lines 9-10: W_{k+1/2,i} = (1/K) sum_j W_{k,j} over the closed neighbourhood, then
+ * W_{k+1,i} = W_{k+1/2,i} - gamma g_i.  volatile keeps every intermediate in float32.       */
+void orc_average_update(const float *sum, uint32_t K, const float *grad, float gamma, uint64_t n,
+                        float *w)
+{
+    volatile float inv_k = 1.0f / (float)K;
+    for (uint64_t j = 0; j < n; ++j) {
+        volatile float avg = sum[j] * inv_k;
+        if (grad) {
+            volatile float step = gamma * grad[j];
+            w[j] = avg - step;
+        } else {
+            w[j] = avg;
+        }
+    }
+}
+
 void orc_bench_polys(const orc_ctx *c, uint32_t B, uint64_t *out)
 {
     for (uint32_t b = 0; b < B; ++b)

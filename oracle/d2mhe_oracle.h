@@ -174,6 +174,13 @@ void orc_bootstrap_share(const orc_ctx *c, const uint64_t *sk_share, const uint6
 void orc_bootstrap_combine(const orc_ctx *c, const uint64_t *ct, const uint64_t *const *shares,
                            uint32_t K, uint32_t C, uint32_t group, uint32_t ct_base, uint64_t *ct_out);
 
+/* ---- the float step of one training iteration (Alg. 2 lines 9-10) ---- */
+/* w[j] = sum[j] * (1/K) - gamma * grad[j], every operation rounded to float32 on its own:
+ * the neighbourhood average from the decoded sum, then the local gradient step.
+ * grad may be NULL when gamma = 0.                                                        */
+void orc_average_update(const float *sum, uint32_t K, const float *grad, float gamma, uint64_t n,
+                        float *w);
+
 /* Uniform benchmark polynomials: out [B][L][N], polynomial b of the batch, limb i.      */
 void orc_bench_polys(const orc_ctx *c, uint32_t B, uint64_t *out);
 /* Batched transform of polys [B][L][N] in place (natural order).                        */

@@ -86,6 +86,7 @@ def lib():
             "orc_bootstrap_alpha": (None, [vp, u32, u32, vp]),
             "orc_bootstrap_share": (None, [vp, vp, vp, u32, u32, u32, u32, vp]),
             "orc_bootstrap_combine": (None, [vp, vp, vp, u32, u32, u32, u32, vp]),
+            "orc_average_update": (None, [vp, u32, vp, C.c_float, u64, vp]),
             "orc_bench_polys": (None, [vp, u32, vp]),
             "orc_ntt_forward_batch": (None, [vp, vp, u32]),
             "orc_ntt_inverse_batch": (None, [vp, vp, u32]),
@@ -96,6 +97,15 @@ def lib():
             fn.restype = res
             fn.argtypes = args
     return _lib
+
+
+def average_update(sum_, K, grad, gamma):
+    """Alg. 2 lines 9-10 in float32: sum * (1/K) - gamma * grad."""
+    sum_ = np.ascontiguousarray(sum_, dtype=np.float32)
+    out = np.zeros_like(sum_)
+    g = None if grad is None else np.ascontiguousarray(grad, dtype=np.float32)
+    lib().orc_average_update(_p(sum_), K, None if g is None else _p(g), gamma, sum_.size, _p(out))
+    return out
 
 
 def _p(a: np.ndarray):

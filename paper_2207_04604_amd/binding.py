@@ -25,6 +25,7 @@ SYMBOLS = [
     "d2mhe_receiver_keygen", "d2mhe_convert_share", "d2mhe_convert_combine", "d2mhe_decrypt",
     "d2mhe_round_convert_scratch_bytes", "d2mhe_round_convert",
     "d2mhe_bootstrap_alpha", "d2mhe_bootstrap_share", "d2mhe_bootstrap_combine",
+    "d2mhe_average_update",
 ]
 
 
@@ -39,7 +40,7 @@ class RoundDesc(C.Structure):
                 ("members", C.POINTER(C.c_uint32)), ("group_ids", C.POINTER(C.c_uint32)),
                 ("pks", C.POINTER(C.c_void_p)), ("num_parties", C.c_uint32),
                 ("sk_shares", C.POINTER(C.c_void_p)), ("grads", C.POINTER(C.c_void_p)),
-                ("out_sums", C.POINTER(C.c_void_p)), ("n_values", C.c_uint64)]
+                ("out_sums", C.POINTER(C.c_void_p)), ("n_values", C.c_uint64), ("ct_base", C.c_uint32)]
 
 
 class ConvertDesc(C.Structure):
@@ -98,6 +99,7 @@ def lib():
         "d2mhe_bootstrap_alpha": (i32, [vp, u32, u32, u32, vp, vp]),
         "d2mhe_bootstrap_share": (i32, [vp, vp, vp, vp, u32, u32, u32, u32, vp, vp]),
         "d2mhe_bootstrap_combine": (i32, [vp, vp, vp, vp, u32, u32, vp, vp]),
+        "d2mhe_average_update": (i32, [vp, u32, vp, C.c_float, u64, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -130,6 +132,10 @@ def make_params(log2_n, q, t, cbd_eta=21, frac_bits=0, max_group=1, seed=0):
     arr = (C.c_uint64 * len(q))(*[int(v) for v in q])
     p = Params(log2_n, len(q), C.cast(arr, C.POINTER(C.c_uint64)), t, cbd_eta, frac_bits, max_group, seed)
     return p, arr
+
+
+def average_update(sum_, K, grad, gamma, n, w, stream=None):
+    _check(lib().d2mhe_average_update(_ptr(sum_), K, _ptr(grad), gamma, n, _ptr(w), stream), "d2mhe_average_update")
 
 
 def workspace_bytes(params: Params) -> int:
@@ -224,7 +230,7 @@ class Context:
     def round_scratch_bytes(self, num_jobs, num_groups, n_values):
         return lib().d2mhe_round_scratch_bytes(self._h, num_jobs, num_groups, n_values)
 
-    def make_round(self, groups, pks, sk_shares, grads, out_sums, n_values, group_ids=None):
+    def make_round(self, groups, pks, sk_shares, grads, out_sums, n_values, group_ids=None, ct_base=0):
         """Marshal a whole-round description once (host tables); returns an opaque object for round().
         groups: list of member lists; pks/out_sums: one buffer per group; sk_shares/grads: by party id
         (list, or dict for sparse ids)."""
@@ -246,7 +252,7 @@ class Context:
         d = RoundDesc(len(groups), keep["offs"], keep["members"], keep["gids"],
                       C.cast(keep["pks"], C.POINTER(C.c_void_p)), P,
                       C.cast(keep["sks"], C.POINTER(C.c_void_p)), C.cast(keep["grads"], C.POINTER(C.c_void_p)),
-                      C.cast(keep["outs"], C.POINTER(C.c_void_p)), n_values)
+                      C.cast(keep["outs"], C.POINTER(C.c_void_p)), n_values, ct_base)
         d._keep = keep
         d.num_jobs = len(flat)
         return d

@@ -616,6 +616,21 @@ d2mhe_status d2mhe_bootstrap_combine(d2mhe_ctx *ctx, const uint64_t *ct, const u
     return engine_ops(ctx)->bootstrap_combine(ctx, ct, sh, K, alpha, C, ct_out, (hipStream_t)stream);
 }
 
+// ---- the float step of one training iteration (Alg. 2 lines 9-10) -----------------------------
+
+d2mhe_status d2mhe_average_update(const float *sum, uint32_t K, const float *grad, float gamma, uint64_t n,
+                                  float *w, void *stream)
+{
+    if (!sum || !w || (!grad && gamma != 0.0f)) return D2MHE_ERR_NULL;
+    if (K == 0) return D2MHE_ERR_RANGE;
+    if (n == 0) return D2MHE_OK;
+    if (n > 0xffffffffull * 256ull) return D2MHE_ERR_RANGE;
+    hipLaunchKernelGGL(k_average_update, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, sum,
+                       1.0f / (float)K, grad, gamma, n, w);
+    if (hipGetLastError() != hipSuccess) return D2MHE_ERR_HIP;
+    return D2MHE_OK;
+}
+
 namespace {
 
 // words of scratch for J (party, group) jobs, G groups, C ciphertext indices; S conversion shares
@@ -680,7 +695,7 @@ d2mhe_status run_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_co
     if (misaligned(scratch)) return D2MHE_ERR_ALIGN;
     if (d->n_values == 0) return D2MHE_OK;
     const uint64_t C64 = (d->n_values + ctx->N - 1) / ctx->N;
-    if (C64 > 0x7fffffffull) return D2MHE_ERR_RANGE;
+    if (C64 > 0x7fffffffull || (uint64_t)d->ct_base + C64 > 0xffffffffull) return D2MHE_ERR_RANGE;
     const uint32_t C = (uint32_t)C64;
     if (scratch_bytes < round_words(ctx, J, G, S, C) * sizeof(uint64_t)) return D2MHE_ERR_WORKSPACE;
 
@@ -709,7 +724,7 @@ d2mhe_status run_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_co
             jobs.party[i] = d->members[j];
             jobs.group[i] = d->group_ids ? d->group_ids[g] : g;
         }
-        d2mhe_status s = ops->encrypt(ctx, true, jobs, n, 0, d->n_values, C, st);
+        d2mhe_status s = ops->encrypt(ctx, true, jobs, n, d->ct_base, d->n_values, C, st);
         if (s != D2MHE_OK) return s;
     }
     if (ev) D2_HIP(ctx, hipEventRecord(ev[1], st));
@@ -744,7 +759,7 @@ d2mhe_status run_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_co
                 jobs.party[i] = d->members[j];
                 jobs.group[i] = d->group_ids ? d->group_ids[g] : g;
             }
-            d2mhe_status s = ops->share(ctx, jobs, n, 0, C, st);
+            d2mhe_status s = ops->share(ctx, jobs, n, d->ct_base, C, st);
             if (s != D2MHE_OK) return s;
         }
         if (ev) D2_HIP(ctx, hipEventRecord(ev[3], st));
@@ -792,7 +807,7 @@ d2mhe_status run_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_co
             jobs.who[i] = member | (receiver << 16);
             jobs.group[i] = d->group_ids ? d->group_ids[f.g] : f.g;
         }
-        d2mhe_status s = ops->convert_share(ctx, jobs, n, 0, C, st);
+        d2mhe_status s = ops->convert_share(ctx, jobs, n, d->ct_base, C, st);
         if (s != D2MHE_OK) return s;
     }
     if (ev) D2_HIP(ctx, hipEventRecord(ev[3], st));
@@ -881,6 +896,7 @@ d2mhe_status d2mhe_round_group(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_
     d.grads = grad_by_party.data();
     d.out_sums = &out_sum;
     d.n_values = n_values;
+    d.ct_base = 0;
     return d2mhe_round(ctx, &d, scratch, scratch_bytes, nullptr, stream);
 }
 

@@ -5,6 +5,9 @@
 #include "philox.hpp"
 #include <stddef.h>
 
+// no fused multiply-add unless written out: float results here are compared bit for bit
+#pragma clang fp contract(off)
+
 namespace d2 {
 
 constexpr int MAX_LIMBS = 16;

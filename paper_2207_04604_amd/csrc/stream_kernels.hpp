@@ -2,6 +2,9 @@
 #pragma once
 #include "kernels.hpp"
 
+// no fused multiply-add unless written out: float results here are compared bit for bit
+#pragma clang fp contract(off)
+
 namespace d2 {
 
 // -------------------------------------------------------------------------------------
@@ -90,6 +93,22 @@ __global__ void __launch_bounds__(256) k_sum_groups(GroupJobs jobs, size_t strid
         acc.y = add_mod(acc.y, v.y, q);
     }
     *(ulonglong2 *)((uint64_t *)jobs.out[job] + i) = acc;
+}
+
+// Alg. 2 lines 9-10 on the decoded neighbourhood sum: w = sum * (1/K) - gamma * grad, every
+// operation rounded to float32 on its own (no contraction), grad may be null when gamma = 0.
+__global__ void __launch_bounds__(256) k_average_update(const float *sum, float inv_k, const float *grad, float gamma,
+                                                        uint64_t n, float *w)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const float avg = sum[i] * inv_k;
+    if (grad) {
+        const float step = gamma * grad[i];      // not contracted (see the pragma at the top)
+        w[i] = avg - step;
+    } else {
+        w[i] = avg;
+    }
 }
 
 }  // namespace d2

@@ -458,6 +458,59 @@ def test_bootstrap_noise_is_reset(orc):
     assert ref.decrypt(s, new_ct) == m
 
 
+def test_average_update_is_ieee_float32(orc):
+    """Alg. 2 lines 9-10: against numpy's float32 arithmetic, plus closed forms."""
+    rng = np.random.default_rng(9)
+    s = rng.normal(0, 5, 1000).astype(np.float32)
+    g = rng.normal(0, 1, 1000).astype(np.float32)
+    for K, gamma in ((1, 0.0), (3, 0.1), (5, 0.01), (7, 1.5)):
+        inv = np.float32(1.0) / np.float32(K)
+        expect = (s * inv).astype(np.float32) - (np.float32(gamma) * g).astype(np.float32)
+        assert np.array_equal(orc.average_update(s, K, g, gamma), expect.astype(np.float32))
+    assert np.array_equal(orc.average_update(s, 1, None, 0.0), s)
+    three = np.array([3.0], dtype=np.float32)
+    assert orc.average_update(three, 3, None, 0.0)[0] == np.float32(3.0) * (np.float32(1.0) / np.float32(3.0))
+
+
+def test_noise_budget_over_many_additions(orc):
+    """Homomorphic additions without a refresh (discussion in Sec. 4.3): the noise of a sum of T
+    fresh ciphertexts stays below T times the bound of one and, together with the wrap term of
+    the plaintext sum (T times Q mod t at most), below Q/(2t); it decrypts.  (With the 30-bit
+    modulus of the smallest configuration the wrap term alone allows only a handful of additions,
+    which is why its encoding clamps to a sum of K_max values.)"""
+    q = orc.find_primes(54, 10, 1)
+    t, K, n = 65537, 4, 1024
+    o = orc.Oracle(10, q, t, 21, 8, K, SEED)
+    keys = [o.keygen_share(k) for k in range(K)]
+    pk = o.aggregate_pk([k[1] for k in keys])
+    s = np.zeros((1, n), dtype=np.uint64)
+    for k in keys:
+        s = (s + k[0]) % np.uint64(q[0])
+    rng = np.random.default_rng(3)
+    T = 40
+    acc, msum, worst_one = None, np.zeros(n, dtype=np.int64), 0
+    lam = o.lambda_mod_q(0)
+
+    def noise(ct, m):
+        y = (orc.ring_mul(ct[0, 1, 0], s[0], q[0], o.psi[0]).astype(object) + ct[0, 0, 0].astype(object)
+             - lam * (m % t).astype(object)) % q[0]
+        y = np.array([int(v) - q[0] if int(v) > q[0] // 2 else int(v) for v in y])
+        # wraps of the plaintext sum add multiples of Q mod t (reading R11): remove them
+        r_t = o.q_mod_t()
+        return np.array([min((abs(v + w * r_t) for w in range(0, T + 1)), default=0) for v in y])
+
+    for i in range(T):
+        m = rng.integers(0, t, n)
+        ct = o.encrypt(pk, m.astype(np.uint64)[None, :], i % K, 0, ct_base=i)
+        worst_one = max(worst_one, int(noise(ct, m).max()))
+        acc = ct if acc is None else o.add(acc, ct)
+        msum += m
+    total = int(noise(acc, msum).max())
+    assert total <= T * worst_one
+    assert total + T * o.q_mod_t() < q[0] // (2 * t)
+    assert np.array_equal(o.decrypt_with_secret(s, acc)[0], (msum % t).astype(np.uint64))
+
+
 def test_noise_identity_and_margin(orc):
     """c0 + c1 s - Lambda m = -mu e_pk + e0 + e1 s exactly (Sec. 3.2 item 3 expanded), and it
     stays below Q/(2t) minus the wrap term (correctness condition under Eq. (2))."""
