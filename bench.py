@@ -5,7 +5,7 @@ A step is one whole round of the hot path (encode + encrypt, homomorphic sum, de
 shares, combine + decode) for every group of the workload, with the float32 gradients and
 all keys already resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu] [--no-ntt] [--no-convert] [--no-bootstrap]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu] [--no-ntt] [--no-convert] [--no-bootstrap] [--no-loop]
 
 Beside the headline round it reports the same round with the paper's own decryption path
 (key switching of every aggregate to its receivers, MBFV.Convert), a collective refresh of the
@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-ntt", action="store_true", help="skip the transform micro-benchmark")
     ap.add_argument("--no-bootstrap", action="store_true", help="skip the collective refresh (MBFV.Bootstrap)")
+    ap.add_argument("--no-loop", action="store_true", help="skip the multi-iteration run (Alg. 2 loop)")
     ap.add_argument("--no-convert", action="store_true",
                     help="skip the round with key switching to the receivers (MBFV.Convert)")
     ap.add_argument("--ntt-reps", type=int, default=20)
@@ -185,6 +186,36 @@ def main():
                      "hbm_algorithmic_GB_per_s": enc_bytes / 1e9 / (enc_ms * 1e-3),
                      "hbm_frac": enc_bytes / 1e9 / (enc_ms * 1e-3) / HBM_PEAK_GBS},
     }
+
+    # ---- training iterations (Alg. 2): round with fresh ciphertext indices, then every node's
+    # float step (average over its neighbourhood, local gradient step) on its own weights
+    if not args.no_loop:
+        owner = cfg.receivers()
+        node_group = {i: gi for gi, rs in enumerate(owner) for i in rs}
+        T_it = 5
+        weights = [g.clone() for g in grads]
+        descs = [ctx.make_round(groups, pks, sks, weights, outs, cfg.n_values, ct_base=it * C_) for it in range(T_it)]
+        le = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+
+        def iterate():
+            for it in range(T_it):
+                ctx.round(descs[it], scratch, nbytes, None, sptr)
+                for i in range(P):
+                    gi = node_group[i]
+                    binding.average_update(outs[gi], len(groups[gi]), grads[i], 0.01, cfg.n_values, weights[i], sptr)
+
+        iterate()
+        torch.cuda.synchronize()
+        le[0].record(stream)
+        iterate()
+        le[1].record(stream)
+        torch.cuda.synchronize()
+        result["training_iterations"] = {
+            "what": f"{T_it} iterations of Alg. 2 on the workload: encrypted round (collective decryption) with "
+                    f"ciphertext indices it*C.., then {P} float steps w = sum/K - gamma*g",
+            "ms_per_iteration": le[0].elapsed_time(le[1]) / T_it}
+        ctx.round(desc, scratch, nbytes, None, sptr)          # leave the scratch as the headline round left it
+        torch.cuda.synchronize()
 
     # ---- MBFV.Bootstrap: the members of group 0 refresh all G*C aggregates the round left in the
     # scratch (same work for each; the first C are group 0's own and are checked after the refresh)
