@@ -4,7 +4,7 @@
 namespace d2 {
 const EngineOps *ops_b_13()
 {
-    static const EngineOps ops = Launch<Engine<ArithB, 13, 4>>::full();
+    static const EngineOps ops = Launch<Engine<ArithB, 13, 3>>::full();
     return &ops;
 }
 }

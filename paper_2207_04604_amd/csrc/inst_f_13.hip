@@ -4,7 +4,7 @@
 namespace d2 {
 const EngineOps *ops_f_13()
 {
-    static const EngineOps ops = Launch<Engine<ArithF, 13, 4>>::full();
+    static const EngineOps ops = Launch<Engine<ArithF, 13, 3>>::full();
     return &ops;
 }
 }
