@@ -132,7 +132,8 @@ def test_convert_wide_primes_ragged_tail_and_extreme_ids():
 
 
 @pytest.mark.parametrize("name,share_sample,ct_sample", [("C1", [(0, 0, 0), (0, 3, 2)], (0, 3)),
-                                                        ("C2", [(0, 0, 0), (7, 0, 2), (15, 0, 4)], (0, 13, 24))])
+                                                        ("C2", [(0, 0, 0), (7, 0, 2), (15, 0, 4)], (0, 13, 24)),
+                                                        ("C3", [(0, 0, 0), (19, 0, 3), (31, 0, 6)], (0, 152))])
 def test_convert_round_in_the_benchmark_launch_shape(name, share_sample, ct_sample):
     """All groups in one d2mhe_round_convert call (what bench.py --convert times): every node
     receives the sum over its closed neighbourhood; sampled conversion shares are recomputed by

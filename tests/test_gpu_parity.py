@@ -333,3 +333,52 @@ def test_whole_round_argument_checks():
         ctx.round(bad, scratch, nbytes * 2)
     assert ei.value.status == B.ERR_RANGE
     ctx.close()
+
+
+def test_global_key_variant_through_the_per_call_interface():
+    """The other reading of Sec. 4.1 ("all nodes encrypt under the same public key"): one collective
+    key over all P nodes, every node encrypts once, node i sums the ciphertexts of its closed
+    neighbourhood, and the decryption of that sum takes a share from every one of the P nodes.
+    The library is set-generic, so this is expressible with the per-call entry points; every object
+    is compared with the oracle's."""
+    from oracle import oracle as O
+    from paper_2207_04604_amd.synth import toy_config
+    cfg = toy_config(10, O.find_primes(36, 10, 2), 65537, 6, 1500, frac_bits=8, topology="circulant", offsets=(1,))
+    P = cfg.parties
+    o, ctx, perm = make_pair(cfg, max_group=P)
+    L, N, n, C_ = o.L, o.N, cfg.n_values, cfg.C
+    grads = cfg.gradients()
+    keys = Keys(o, ctx, perm, range(P), check=False)
+    everyone = list(range(P))
+    opk, dpk = keys.group_pk(everyone, perm)
+    dcts, octs = [], []
+    for k in everyone:                                   # one encryption per node, group id 0
+        dpt = dzeros(C_ * N)
+        ctx.encode(to_dev(grads[k]), n, dpt, C_)
+        dct = dzeros(C_ * 2 * L * N)
+        ctx.encrypt(dpk, dpt, C_, k, 0, 0, dct)
+        oct_ = o.encrypt(opk, o.encode(grads[k]), k, 0, 0)
+        assert np.array_equal(to_host(dct, oct_.shape), to_eval(o, perm, oct_))
+        dcts.append(dct)
+        octs.append(oct_)
+    for i, hood in enumerate(cfg.groups()):              # node i's closed neighbourhood
+        dagg, oagg = dcts[hood[0]].clone(), octs[hood[0]]
+        for j in hood[1:]:
+            ctx.add(dagg, dcts[j], C_)
+            oagg = o.add(oagg, octs[j])
+        dshares, oshares = [], []
+        for k in everyone:                               # shares from all P nodes, indexed by the receiver
+            dsh = dzeros(C_ * L * N)
+            ctx.partial_decrypt(keys.sk[k], dagg, C_, k, 1 + i, 0, dsh)
+            osh = o.partial_decrypt(keys.osk[k], oagg, k, 1 + i, 0)
+            assert np.array_equal(to_host(dsh, osh.shape), to_eval(o, perm, osh))
+            dshares.append(dsh)
+            oshares.append(osh)
+        dout = dzeros(C_ * N)
+        ctx.combine(dagg, dshares, C_, dout)
+        assert np.array_equal(to_host(dout, (C_, N)), o.combine(oagg, oshares))
+        dres = torch.zeros(n, dtype=torch.float32, device=DEV)
+        ctx.decode(dout, C_, n, dres)
+        expect = fixed_point_sum([grads[k] for k in hood], cfg.frac_bits, o.encode_clamp())
+        assert np.array_equal(dres.cpu().numpy(), expect), f"node {i}"
+    ctx.close()
