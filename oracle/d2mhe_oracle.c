@@ -554,6 +554,41 @@ int orc_decode(const orc_ctx *c, const uint64_t *pt, uint32_t C, uint64_t n_valu
     return 0;
 }
 
+/* The same fixed point without the slot transform: value c N + j is coefficient j.          */
+int orc_encode_coefficients(const orc_ctx *c, const float *grad, uint64_t n_values, uint64_t *pt,
+                            uint32_t C)
+{
+    size_t n = c->n;
+    uint64_t t = c->p.t;
+    if (!t || n_values > (uint64_t)C * n) return -1;
+    float scale = ldexpf(1.0f, (int)c->p.frac_bits);
+    float bound = (float)c->clamp;
+    for (uint64_t idx = 0; idx < (uint64_t)C * n; ++idx) {
+        int64_t r = 0;
+        if (idx < n_values) {
+            float v = grad[idx];
+            float rf = isnan(v) ? 0.0f : rintf(v * scale);
+            if (rf > bound) rf = bound;
+            if (rf < -bound) rf = -bound;
+            r = (int64_t)rf;
+        }
+        pt[idx] = r >= 0 ? (uint64_t)r : t - (uint64_t)(-r);
+    }
+    return 0;
+}
+
+int orc_decode_coefficients(const orc_ctx *c, const uint64_t *pt, uint32_t C, uint64_t n_values,
+                            float *out)
+{
+    uint64_t t = c->p.t;
+    if (!t || n_values > (uint64_t)C * c->n) return -1;
+    for (uint64_t idx = 0; idx < n_values; ++idx) {
+        int64_t v = pt[idx] > (t - 1) / 2 ? (int64_t)pt[idx] - (int64_t)t : (int64_t)pt[idx];
+        out[idx] = ldexpf((float)v, -(int)c->p.frac_bits);
+    }
+    return 0;
+}
+
 /* BFV.Encrypt: ct = (Lambda x + mu p0 + e0, mu p1 + e1), mu ternary, e0, e1 from chi.    */
 void orc_encrypt(const orc_ctx *c, const uint64_t *pk, const uint64_t *pt, uint32_t C,
                  uint32_t party, uint32_t group, uint32_t ct_base, uint64_t *ct)

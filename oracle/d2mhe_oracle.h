@@ -121,6 +121,12 @@ void orc_aggregate_pk(const orc_ctx *c, const uint64_t *const *pk0_shares, uint3
 /* float gradient -> fixed point -> slots -> plaintext polynomials pt [C][N] in [0,t).   */
 int orc_encode(const orc_ctx *c, const float *grad, uint64_t n_values, uint64_t *pt,
                uint32_t C);
+/* Coefficient packing: the same fixed point, but value c N + j is coefficient j of plaintext c
+ * (no slot structure; enough for a workload that only adds).  pt [C][N].                  */
+int orc_encode_coefficients(const orc_ctx *c, const float *grad, uint64_t n_values, uint64_t *pt,
+                            uint32_t C);
+int orc_decode_coefficients(const orc_ctx *c, const uint64_t *pt, uint32_t C, uint64_t n_values,
+                            float *out);
 /* BFV.Encrypt under pk for ciphertext indices ct_base..ct_base+C-1: ct [C][2][L][N].    */
 void orc_encrypt(const orc_ctx *c, const uint64_t *pk, const uint64_t *pt, uint32_t C,
                  uint32_t party, uint32_t group, uint32_t ct_base, uint64_t *ct);

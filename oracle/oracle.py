@@ -74,6 +74,8 @@ def lib():
             "orc_keygen_share": (None, [vp, u32, vp, vp, vp, vp]),
             "orc_aggregate_pk": (None, [vp, vp, u32, vp]),
             "orc_encode": (i32, [vp, vp, u64, vp, u32]),
+            "orc_encode_coefficients": (i32, [vp, vp, u64, vp, u32]),
+            "orc_decode_coefficients": (i32, [vp, vp, u32, u64, vp]),
             "orc_encrypt": (None, [vp, vp, vp, u32, u32, u32, u32, vp]),
             "orc_add": (None, [vp, vp, vp, u32]),
             "orc_partial_decrypt": (None, [vp, vp, vp, u32, u32, u32, u32, vp]),
@@ -268,6 +270,21 @@ class Oracle:
         if lib().orc_encode(self._h, _p(grad), grad.size, _p(pt), C_) != 0:
             raise ValueError("encode: bad sizes")
         return pt
+
+    def encode_coefficients(self, grad, C_=None):
+        grad = np.ascontiguousarray(grad, dtype=np.float32)
+        C_ = self.num_ct(grad.size) if C_ is None else C_
+        pt = np.zeros((C_, self.N), dtype=np.uint64)
+        if lib().orc_encode_coefficients(self._h, _p(grad), grad.size, _p(pt), C_) != 0:
+            raise ValueError("encode: bad sizes")
+        return pt
+
+    def decode_coefficients(self, pt, n_values):
+        pt = _u64(pt)
+        out = np.zeros(n_values, dtype=np.float32)
+        if lib().orc_decode_coefficients(self._h, _p(pt), pt.shape[0], n_values, _p(out)) != 0:
+            raise ValueError("decode: bad sizes")
+        return out
 
     def encrypt(self, pk, pt, party, group, ct_base=0):
         pk, pt = _u64(pk), _u64(pt)

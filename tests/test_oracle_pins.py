@@ -594,6 +594,36 @@ def test_encode_decode_fixed_point(orc):
     assert np.array_equal((a + b) % 65537, s)
 
 
+def test_coefficient_packing_cross_check(orc):
+    """The two encodings are tied by the slot transform (slot encoding = inverse transform mod t of the
+    coefficient encoding), and a whole round decodes to the same sums with either."""
+    q = orc.find_primes(36, 6, 2)
+    t, K, n_values = 257, 3, 150
+    o = orc.Oracle(6, q, t, 21, 2, K, SEED)
+    rng = np.random.default_rng(12)
+    grads = [rng.normal(0, 4.0, n_values).astype(np.float32) for _ in range(K)]
+    grads[0][:4] = [np.nan, np.inf, -np.inf, 0.375]
+    for g in grads:
+        pc, ps = o.encode_coefficients(g), o.encode(g)
+        for c in range(pc.shape[0]):
+            assert np.array_equal(orc.ntt_inverse(pc[c], t, o.psi_t), ps[c])
+        assert np.array_equal(o.decode_coefficients(pc, n_values), o.decode(ps, n_values))
+    keys = [o.keygen_share(k) for k in range(K)]
+    pk = o.aggregate_pk([k[1] for k in keys])
+    sums = []
+    for enc, dec in ((o.encode, o.decode), (o.encode_coefficients, o.decode_coefficients)):
+        agg = None
+        for k in range(K):
+            ct = o.encrypt(pk, enc(grads[k]), k, 0, 0)
+            agg = ct if agg is None else o.add(agg, ct)
+        shares = [o.partial_decrypt(keys[k][0], agg, k, 0, 0) for k in range(K)]
+        sums.append(dec(o.combine(agg, shares), n_values))
+    assert np.array_equal(sums[0], sums[1])
+    clamp = o.encode_clamp()
+    fixed = sum(np.clip(np.where(np.isnan(g), 0, np.rint(g * np.float32(4.0))), -clamp, clamp).astype(np.int64) for g in grads)
+    assert np.array_equal(sums[1], (fixed.astype(np.float32) * np.float32(0.25)))
+
+
 def test_fixed_point_error_bound(orc):
     o, _, _ = _toy(orc, 6, 36, 2, 65537, 1, 13)
     rng = np.random.default_rng(7)
