@@ -51,6 +51,7 @@ def main():
     ap.add_argument("--no-ntt", action="store_true", help="skip the transform micro-benchmark")
     ap.add_argument("--no-bootstrap", action="store_true", help="skip the collective refresh (MBFV.Bootstrap)")
     ap.add_argument("--no-loop", action="store_true", help="skip the multi-iteration run (Alg. 2 loop)")
+    ap.add_argument("--no-coeff", action="store_true", help="skip the round with coefficient packing")
     ap.add_argument("--no-convert", action="store_true",
                     help="skip the round with key switching to the receivers (MBFV.Convert)")
     ap.add_argument("--ntt-reps", type=int, default=20)
@@ -186,6 +187,38 @@ def main():
                      "hbm_algorithmic_GB_per_s": enc_bytes / 1e9 / (enc_ms * 1e-3),
                      "hbm_frac": enc_bytes / 1e9 / (enc_ms * 1e-3) / HBM_PEAK_GBS},
     }
+
+    # ---- the same round with coefficient packing (value j of a ciphertext is coefficient j): an
+    # addition-only workload does not need the slot structure, so both transforms modulo t go away
+    if not args.no_coeff:
+        pdesc = ctx.make_round(groups, pks, sks, grads, outs, cfg.n_values, packing=1)
+        psteps = max(1, min(args.steps, 10))
+        for o_ in outs:
+            o_.zero_()
+        for _ in range(min(args.warmup, 2)):
+            ctx.round(pdesc, scratch, nbytes, None, sptr)
+        torch.cuda.synchronize()
+        pev = [new_events() for _ in range(psteps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(psteps):
+            ctx.round(pdesc, scratch, nbytes, [e.cuda_event for e in pev[i]], sptr)
+        torch.cuda.synchronize()
+        pms = (time.perf_counter() - t0) * 1e3 / psteps
+        pphase = [sum(ev[i].elapsed_time(ev[i + 1]) for ev in pev) / psteps for i in range(4)]
+        for gi in (0, G - 1):
+            acc = np.zeros(cfg.n_values, dtype=np.int64)
+            for k in groups[gi]:
+                acc += np.clip(np.rint(grads_host[k] * np.float32(2.0 ** cfg.frac_bits)), -clamp, clamp).astype(np.int64)
+            if not np.array_equal(outs[gi].cpu().numpy(), acc.astype(np.float32) * np.float32(2.0 ** -cfg.frac_bits)):
+                print("bench.py: coefficient-packed result differs from the fixed-point sum", file=sys.stderr)
+                sys.exit(8)
+        result["coefficient_packing_round"] = {
+            "what": "the whole round with value j of a ciphertext as coefficient j (no transform modulo t in "
+                    "encode or decode); same sums",
+            "ms_per_step": pms, "steps": psteps, "fresh_ct_per_s": fresh / (pms * 1e-3),
+            "phase_ms": {"encode_encrypt": pphase[0], "aggregate": pphase[1], "shares": pphase[2],
+                         "combine_decode": pphase[3]}}
 
     # ---- training iterations (Alg. 2): round with fresh ciphertext indices, then every node's
     # float step (average over its neighbourhood, local gradient step) on its own weights

@@ -136,6 +136,15 @@ d2mhe_status d2mhe_combine(d2mhe_ctx *ctx, const uint64_t *ct, const uint64_t *c
 d2mhe_status d2mhe_decode(d2mhe_ctx *ctx, const uint64_t *pt, uint32_t C, uint64_t n_values,
                           float *out, void *stream);
 
+/* Coefficient packing, the cheaper encoding for a workload that only adds: value c*N+j is
+ * coefficient j of plaintext c (same fixed point, clamp and tail rule), so neither side needs
+ * the transform modulo t.  Sums of ciphertexts decode to the same sums as with slots; the two
+ * encodings must not be mixed within one sum.                                             */
+d2mhe_status d2mhe_encode_coefficients(d2mhe_ctx *ctx, const float *grad, uint64_t n_values,
+                                       uint64_t *pt, uint32_t C, void *stream);
+d2mhe_status d2mhe_decode_coefficients(d2mhe_ctx *ctx, const uint64_t *pt, uint32_t C,
+                                       uint64_t n_values, float *out, void *stream);
+
 /* ---- fused round (same results as the calls above) ---------------------------------------------- */
 /* One exchange round of Alg. 2 (lines 6-9) for every group at once.  Group g has members
  * members[group_offsets[g] .. group_offsets[g+1]) (party ids); a (party, group) pair is a
@@ -152,6 +161,8 @@ typedef struct {
     const float *const *grads;       /* [P] gradient by party id, n_values floats each      */
     float *const *out_sums;          /* [G] result per group, n_values floats each          */
     uint64_t n_values;
+    uint32_t packing;                /* 0: value j of a ciphertext is slot j (default);
+                                        1: it is coefficient j (see d2mhe_encode_coefficients)  */
     uint32_t ct_base;                /* first ciphertext index of this round: the randomness of
                                         ciphertext c is indexed by ct_base + c; a training loop
                                         passes iteration * C so that no index is used twice  */

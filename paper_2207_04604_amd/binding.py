@@ -25,7 +25,7 @@ SYMBOLS = [
     "d2mhe_receiver_keygen", "d2mhe_convert_share", "d2mhe_convert_combine", "d2mhe_decrypt",
     "d2mhe_round_convert_scratch_bytes", "d2mhe_round_convert",
     "d2mhe_bootstrap_alpha", "d2mhe_bootstrap_share", "d2mhe_bootstrap_combine",
-    "d2mhe_average_update",
+    "d2mhe_average_update", "d2mhe_encode_coefficients", "d2mhe_decode_coefficients",
 ]
 
 
@@ -40,7 +40,8 @@ class RoundDesc(C.Structure):
                 ("members", C.POINTER(C.c_uint32)), ("group_ids", C.POINTER(C.c_uint32)),
                 ("pks", C.POINTER(C.c_void_p)), ("num_parties", C.c_uint32),
                 ("sk_shares", C.POINTER(C.c_void_p)), ("grads", C.POINTER(C.c_void_p)),
-                ("out_sums", C.POINTER(C.c_void_p)), ("n_values", C.c_uint64), ("ct_base", C.c_uint32)]
+                ("out_sums", C.POINTER(C.c_void_p)), ("n_values", C.c_uint64), ("packing", C.c_uint32),
+                ("ct_base", C.c_uint32)]
 
 
 class ConvertDesc(C.Structure):
@@ -100,6 +101,8 @@ def lib():
         "d2mhe_bootstrap_share": (i32, [vp, vp, vp, vp, u32, u32, u32, u32, vp, vp]),
         "d2mhe_bootstrap_combine": (i32, [vp, vp, vp, vp, u32, u32, vp, vp]),
         "d2mhe_average_update": (i32, [vp, u32, vp, C.c_float, u64, vp, vp]),
+        "d2mhe_encode_coefficients": (i32, [vp, vp, u64, vp, u32, vp]),
+        "d2mhe_decode_coefficients": (i32, [vp, vp, u32, u64, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -209,6 +212,14 @@ class Context:
     def encode(self, grad, n_values, pt, C_, stream=None):
         _check(lib().d2mhe_encode(self._h, _ptr(grad), n_values, _ptr(pt), C_, stream), "d2mhe_encode")
 
+    def encode_coefficients(self, grad, n_values, pt, C_, stream=None):
+        _check(lib().d2mhe_encode_coefficients(self._h, _ptr(grad), n_values, _ptr(pt), C_, stream),
+               "d2mhe_encode_coefficients")
+
+    def decode_coefficients(self, pt, C_, n_values, out, stream=None):
+        _check(lib().d2mhe_decode_coefficients(self._h, _ptr(pt), C_, n_values, _ptr(out), stream),
+               "d2mhe_decode_coefficients")
+
     def encrypt(self, pk, pt, C_, party, group, ct_base, ct, stream=None):
         _check(lib().d2mhe_encrypt(self._h, _ptr(pk), _ptr(pt), C_, party, group, ct_base, _ptr(ct), stream),
                "d2mhe_encrypt")
@@ -230,7 +241,8 @@ class Context:
     def round_scratch_bytes(self, num_jobs, num_groups, n_values):
         return lib().d2mhe_round_scratch_bytes(self._h, num_jobs, num_groups, n_values)
 
-    def make_round(self, groups, pks, sk_shares, grads, out_sums, n_values, group_ids=None, ct_base=0):
+    def make_round(self, groups, pks, sk_shares, grads, out_sums, n_values, group_ids=None, ct_base=0,
+                   packing=0):
         """Marshal a whole-round description once (host tables); returns an opaque object for round().
         groups: list of member lists; pks/out_sums: one buffer per group; sk_shares/grads: by party id
         (list, or dict for sparse ids)."""
@@ -252,7 +264,7 @@ class Context:
         d = RoundDesc(len(groups), keep["offs"], keep["members"], keep["gids"],
                       C.cast(keep["pks"], C.POINTER(C.c_void_p)), P,
                       C.cast(keep["sks"], C.POINTER(C.c_void_p)), C.cast(keep["grads"], C.POINTER(C.c_void_p)),
-                      C.cast(keep["outs"], C.POINTER(C.c_void_p)), n_values, ct_base)
+                      C.cast(keep["outs"], C.POINTER(C.c_void_p)), n_values, packing, ct_base)
         d._keep = keep
         d.num_jobs = len(flat)
         return d

@@ -435,6 +435,30 @@ d2mhe_status d2mhe_decode(d2mhe_ctx *ctx, const uint64_t *pt, uint32_t C, uint64
     return engine_ops(ctx)->decode(ctx, pt, C, n_values, out, (hipStream_t)stream);
 }
 
+// Coefficient packing (value j of a ciphertext is coefficient j): the same launchers with the
+// packing flag set in a private copy of the context.
+d2mhe_status d2mhe_encode_coefficients(d2mhe_ctx *ctx, const float *grad, uint64_t n_values, uint64_t *pt,
+                                       uint32_t C, void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    d2mhe_ctx local = *ctx;
+    local.rc.coeff_packing = 1;
+    const d2mhe_status s = d2mhe_encode(&local, grad, n_values, pt, C, stream);
+    ctx->last_hip = local.last_hip;
+    return s;
+}
+
+d2mhe_status d2mhe_decode_coefficients(d2mhe_ctx *ctx, const uint64_t *pt, uint32_t C, uint64_t n_values,
+                                       float *out, void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    d2mhe_ctx local = *ctx;
+    local.rc.coeff_packing = 1;
+    const d2mhe_status s = d2mhe_decode(&local, pt, C, n_values, out, stream);
+    ctx->last_hip = local.last_hip;
+    return s;
+}
+
 d2mhe_status d2mhe_encrypt(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_t *pt, uint32_t C, uint32_t party,
                            uint32_t group, uint32_t ct_base, uint64_t *ct, void *stream)
 {
@@ -850,11 +874,25 @@ size_t d2mhe_round_convert_scratch_bytes(const d2mhe_ctx *ctx, uint32_t num_jobs
     return round_words(ctx, num_jobs, num_groups, num_shares, C) * sizeof(uint64_t);
 }
 
+// The packing of the round travels in a private copy of the context (the launchers read the
+// per-context constants from it).
+d2mhe_status run_round_packed(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_convert_desc *conv,
+                              void *scratch, size_t scratch_bytes, void *const *phase_events, void *stream)
+{
+    if (!d) return D2MHE_ERR_NULL;
+    if (d->packing > 1) return D2MHE_ERR_RANGE;
+    d2mhe_ctx local = *ctx;
+    local.rc.coeff_packing = d->packing;
+    const d2mhe_status s = run_round(&local, d, conv, scratch, scratch_bytes, phase_events, stream);
+    ctx->last_hip = local.last_hip;
+    return s;
+}
+
 d2mhe_status d2mhe_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, void *scratch, size_t scratch_bytes,
                          void *const *phase_events, void *stream)
 {
     D2_NEED_SCHEME(ctx);
-    return run_round(ctx, d, nullptr, scratch, scratch_bytes, phase_events, stream);
+    return run_round_packed(ctx, d, nullptr, scratch, scratch_bytes, phase_events, stream);
 }
 
 d2mhe_status d2mhe_round_convert(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_convert_desc *conv,
@@ -862,7 +900,7 @@ d2mhe_status d2mhe_round_convert(d2mhe_ctx *ctx, const d2mhe_round_desc *d, cons
 {
     D2_NEED_SCHEME(ctx);
     if (!conv) return D2MHE_ERR_NULL;
-    return run_round(ctx, d, conv, scratch, scratch_bytes, phase_events, stream);
+    return run_round_packed(ctx, d, conv, scratch, scratch_bytes, phase_events, stream);
 }
 
 d2mhe_status d2mhe_round_group(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_t *const *sk_shares,
@@ -897,6 +935,7 @@ d2mhe_status d2mhe_round_group(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_
     d.out_sums = &out_sum;
     d.n_values = n_values;
     d.ct_base = 0;
+    d.packing = 0;
     return d2mhe_round(ctx, &d, scratch, scratch_bytes, nullptr, stream);
 }
 

@@ -74,6 +74,7 @@ struct RoundConst {
     float scale;         // 2^f
     float inv_scale;     // 2^-f
     PhiloxKey key;
+    uint32_t coeff_packing;   // 0: value j of a ciphertext is slot j (default); 1: it is coefficient j
 };
 
 struct PtrList {
@@ -383,6 +384,8 @@ D2_DEV int32_t sbyte(uint32_t w, int i) { return (int32_t)(int8_t)(w >> (8 * i))
 // -------------------------------------------------------------------------------------
 // Fixed point + slots (encode) as a device step: leaves the plaintext polynomial of
 // ciphertext index c in registers in pass-0 (natural) ownership, values in [0, t).
+// With rc.coeff_packing the values are the coefficients themselves (an addition-only workload
+// never needs the slot structure): no transform on either side.
 // -------------------------------------------------------------------------------------
 template <class ENG>
 D2_DEV void encode_to_regs(uint32_t (&m)[ENG::E], uint64_t *lds, int tid, const float *grad, uint64_t first,
@@ -391,17 +394,22 @@ D2_DEV void encode_to_regs(uint32_t (&m)[ENG::E], uint64_t *lds, int tid, const 
     typedef typename ENG::A A;
     const uint64_t t = tt.q;
     const typename A::Mod md = A::mod(t, tt.one_s);
-    __syncthreads();
-    for (int j = tid; j < ENG::NB; j += ENG::T) {
-        uint64_t gi = first + (uint64_t)j;
+    auto fixed = [&](uint64_t gi) -> uint64_t {          // value gi as a residue mod t
         float v = gi < n_values ? grad[gi] : 0.0f;
         float r = (v != v) ? 0.0f : __builtin_rintf(v * rc.scale);
         float bound = (float)rc.clamp;
         r = r > bound ? bound : r;
         r = r < -bound ? -bound : r;
         int32_t z = (int32_t)r;
-        lds[ENG::phys(j)] = z >= 0 ? (uint64_t)z : t - (uint64_t)(uint32_t)(-z);
+        return z >= 0 ? (uint64_t)z : t - (uint64_t)(uint32_t)(-z);
+    };
+    if (rc.coeff_packing) {                              // coefficient packing: no transform
+#pragma unroll
+        for (int k = 0; k < ENG::E; ++k) m[k] = (uint32_t)fixed(first + (uint64_t)ENG::coef_pos(k, tid));
+        return;
     }
+    __syncthreads();
+    for (int j = tid; j < ENG::NB; j += ENG::T) lds[ENG::phys(j)] = fixed(first + (uint64_t)j);
     __syncthreads();
     // slot j is the evaluation xhat[j], which the engine keeps at block index bitrev(j)
     typename A::elem x[ENG::E];
@@ -421,6 +429,17 @@ D2_DEV void decode_from_regs(uint32_t (&m)[ENG::E], uint64_t *lds, int tid, floa
     typedef typename ENG::A A;
     const uint64_t t = tt.q;
     const typename A::Mod md = A::mod(t, tt.one_s);
+    if (rc.coeff_packing) {                              // coefficient packing: no transform
+#pragma unroll
+        for (int k = 0; k < ENG::E; ++k) {
+            const uint64_t gi = first + (uint64_t)ENG::coef_pos(k, tid), z = m[k];
+            if (gi < n_values) {
+                const int32_t c = z > (t - 1) / 2 ? (int32_t)((int64_t)z - (int64_t)t) : (int32_t)z;
+                out[gi] = (float)c * rc.inv_scale;
+            }
+        }
+        return;
+    }
     typename A::elem x[ENG::E];
 #pragma unroll
     for (int k = 0; k < ENG::E; ++k) x[k] = A::from_canon((uint64_t)m[k], md);
