@@ -382,3 +382,44 @@ def test_global_key_variant_through_the_per_call_interface():
         expect = fixed_point_sum([grads[k] for k in hood], cfg.frac_bits, o.encode_clamp())
         assert np.array_equal(dres.cpu().numpy(), expect), f"node {i}"
     ctx.close()
+
+
+def test_largest_group_of_64_members():
+    """The largest neighbourhood the library accepts (64 members): per-call objects against the oracle, the fused
+    round for that group and for two such groups in one call (128 jobs: two launches per phase), and one more
+    member refused on the host."""
+    q = O.find_primes(36, 10, 2)
+    cfg = toy_config(10, q, 65537, parties=64, n_values=1024 + 19, frac_bits=6)
+    o, ctx, perm = make_pair(cfg, max_group=64)
+    assert o.encode_clamp() == 32768 // 64
+    rng = np.random.default_rng(64)
+    grads = {k: rng.normal(0, 3.0, cfg.n_values).astype(np.float32) for k in range(64)}
+    grads[5][:3] = [1e9, -1e9, np.nan]                  # clamped: 64 such terms still cannot wrap
+    members = list(range(64))
+    keys = Keys(o, ctx, perm, members, check=False)
+    dpk, opk, _ = run_calls_and_compare(cfg, o, ctx, perm, keys, members, 9, grads, check_cts=False)
+    res, _ = run_fused(ctx, o, dpk, keys, members, 9, grads, cfg.n_values)
+    expect = fixed_point_sum([grads[k] for k in members], 6, o.encode_clamp())
+    assert np.array_equal(res, expect)
+    # two groups over the same 64 parties (different group ids, hence different randomness), one call
+    outs = [torch.zeros(cfg.n_values, dtype=torch.float32, device=DEV) for _ in range(2)]
+    nbytes = ctx.round_scratch_bytes(128, 2, cfg.n_values)
+    scratch = dzeros(nbytes // 8)
+    rev = members[::-1]
+    desc = ctx.make_round([members, rev], [dpk, dpk], [keys.sk[k] for k in members], [to_dev(grads[k]) for k in members],
+                          outs, cfg.n_values, group_ids=[9, 10])
+    ctx.round(desc, scratch, nbytes)
+    torch.cuda.synchronize()
+    assert np.array_equal(outs[0].cpu().numpy(), expect) and np.array_equal(outs[1].cpu().numpy(), expect)
+    L, N, C_ = o.L, o.N, cfg.C
+    agg = to_host(scratch[128 * C_ * 2 * L * N:130 * C_ * 2 * L * N], (2, C_, 2, L, N))
+    oagg = None
+    for k in rev:
+        oct_ = o.encrypt(opk, o.encode(grads[k]), k, 10, 0)
+        oagg = oct_ if oagg is None else o.add(oagg, oct_)
+    assert np.array_equal(agg[1], to_eval(o, perm, oagg))
+    guard = dzeros(16)
+    with pytest.raises(B.D2mheError) as ei:
+        ctx.combine(guard, [guard] * 65, 1, guard)
+    assert ei.value.status == B.ERR_RANGE
+    ctx.close()
