@@ -250,7 +250,7 @@ class Context:
         offs = [0]
         for g in groups:
             offs.append(offs[-1] + len(g))
-        P = max(flat) + 1
+        P = max(flat) + 1 if flat else 0
         get = (lambda tbl, k: tbl.get(k)) if isinstance(sk_shares, dict) else (lambda tbl, k: tbl[k] if k < len(tbl) else None)
         keep = {
             "offs": (C.c_uint32 * len(offs))(*offs),

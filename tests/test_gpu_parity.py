@@ -332,6 +332,18 @@ def test_whole_round_argument_checks():
     with pytest.raises(B.D2mheError) as ei:           # 5 members > max_group = 4
         ctx.round(bad, scratch, nbytes * 2)
     assert ei.value.status == B.ERR_RANGE
+    sks, dgr = [keys.sk[k] for k in range(4)], [to_dev(g) for g in grads]
+    for groups_, pks_, outs_, status in (([], [], [], B.ERR_RANGE),                           # no group
+                                         ([[]], [pks[0][1]], outs, B.ERR_RANGE),               # an empty group
+                                         ([[0, 1, 7]], [pks[0][1]], outs, B.ERR_NULL)):        # a member without key
+        with pytest.raises(B.D2mheError) as ei:
+            ctx.round(ctx.make_round(groups_, pks_, sks, dgr, outs_, cfg.n_values), scratch, nbytes)
+        assert ei.value.status == status
+    # a round over zero values is accepted and writes nothing
+    before = outs[0].clone()
+    ctx.round(ctx.make_round([[0, 1, 2, 3]], [pks[0][1]], sks, dgr, outs, 0), scratch, nbytes)
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], before)
     ctx.close()
 
 
