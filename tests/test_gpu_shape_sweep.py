@@ -1,0 +1,60 @@
+"""Every (arithmetic back-end, ring degree) pair the library instantiates, against the oracle: the three
+back-ends are chosen by the largest prime (< 2^44, < 2^55, < 2^61), the kernel shapes by log2 N.  The five
+benchmark configurations cover five of these pairs; this sweep covers the rest with small seeded inputs
+(two or three ciphertexts, a ragged tail), every intermediate object compared bit for bit."""
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2207_04604_amd.synth import toy_config
+
+from gpu_util import Keys, dzeros, make_ctx, make_pair, to_dev, to_eval, to_host
+from test_gpu_parity import fixed_point_sum, run_calls_and_compare, run_fused
+
+pytestmark = pytest.mark.gpu
+
+
+# (log2 N, prime bits, limbs); primes "of b bits" lie just below 2^b: 44 bits is the widest the double-precision
+# back-end takes, 45 to 55 go to the second, 56 to 61 to the third.  Small primes come in pairs so that the
+# plaintext modulus leaves room for the noise.
+SCHEME_SHAPES = [(10, 44, 2), (10, 45, 1), (10, 55, 2), (10, 56, 1), (10, 61, 2), (11, 36, 3), (11, 44, 1), (11, 61, 2),
+                 (12, 45, 2), (12, 55, 1), (12, 61, 2), (13, 30, 2), (13, 44, 2), (13, 56, 1), (13, 61, 2), (14, 36, 2),
+                 (14, 44, 1), (14, 61, 2)]
+
+
+@pytest.mark.parametrize("log2n,bits,L", SCHEME_SHAPES)
+def test_round_objects_for_every_backend_and_degree(log2n, bits, L):
+    N = 1 << log2n
+    t = 12289 if log2n <= 11 else 65537
+    q = O.find_primes(bits, log2n, L)
+    cfg = toy_config(log2n, q, t, parties=3, n_values=N + 37, frac_bits=5)
+    o, ctx, perm = make_pair(cfg, max_group=3)
+    rng = np.random.default_rng(1000 * log2n + bits)
+    grads = {k: rng.normal(0, 6.0, cfg.n_values).astype(np.float32) for k in range(3)}
+    keys = Keys(o, ctx, perm, range(3))
+    dpk, opk, _ = run_calls_and_compare(cfg, o, ctx, perm, keys, [0, 1, 2], 4, grads, ct_base=9)
+    res, _ = run_fused(ctx, o, dpk, keys, [0, 1, 2], 4, grads, cfg.n_values)
+    assert np.array_equal(res, fixed_point_sum([grads[k] for k in range(3)], 5, o.encode_clamp()))
+    ctx.close()
+
+
+@pytest.mark.parametrize("log2n,bits,L,batch", [(15, 36, 2, 3), (15, 55, 1, 2), (15, 61, 2, 2), (16, 44, 1, 3), (16, 45, 2, 2),
+                                                (16, 56, 1, 9), (10, 61, 1, 5), (12, 55, 3, 2), (14, 30, 1, 2)])
+def test_transforms_for_every_backend_and_degree(log2n, bits, L, batch):
+    """Transform-only contexts (t = 0), including the two-kernel path for N > 16384 with batches that do not
+    fill a workgroup's share of polynomials."""
+    N = 1 << log2n
+    q = O.find_primes(bits, log2n, L)
+    o = O.Oracle(log2n, q, 0, 21, 0, 1, 77)
+    ctx = make_ctx(log2n, q, 0, seed=77)
+    perm = ctx.index_map()
+    assert sorted(perm.tolist()) == list(range(N))
+    polys = o.bench_polys(batch)
+    for i in range(L):
+        polys[0, i, :4] = [0, 1, q[i] - 1, q[i] - 2]
+    d = to_dev(polys.reshape(-1))
+    ctx.ntt_forward(d, batch)
+    assert np.array_equal(to_host(d, polys.shape), to_eval(o, perm, polys)), "forward transform"
+    ctx.ntt_inverse(d, batch)
+    assert np.array_equal(to_host(d, polys.shape), polys), "inverse transform"
+    ctx.close()
