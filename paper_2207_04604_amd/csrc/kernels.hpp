@@ -694,7 +694,9 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
     typedef typename ENG::A A;
     constexpr int E = ENG::E;
     const int tid = threadIdx.x;
-    const uint32_t c = blockIdx.x, L = rc.L;
+    // ciphertext indices (and, in the whole-round kernels, jobs) from the last to the first: what the
+    // share kernel wrote last is still in the memory-side cache
+    const uint32_t c = gridDim.x - 1 - blockIdx.x, L = rc.L;
     const size_t LN = (size_t)L * ENG::NB;
     const size_t share_ct = (MODE == COMBINE_COLLECTIVE ? 1 : 2) * LN;       // words of one share per ciphertext index
     const uint64_t *c0 = ct + (size_t)c * 2 * LN;
@@ -846,7 +848,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_combine_decode(GroupJobs
                                                            const LimbTab *tabs, RoundConst rc)
 {
     __shared__ uint64_t lds[ENG::LDS_WORDS];
-    const uint32_t job = blockIdx.y;
+    const uint32_t job = gridDim.y - 1 - blockIdx.y;
     const uint64_t *first = jobs.first[job];
     combine_body<ENG, true, COMBINE_COLLECTIVE>(lds, jobs.ct[job], [&](uint32_t j) { return first + (size_t)j * stride; },
                                    jobs.K[job], (const uint64_t *)nullptr, false, (uint64_t *)nullptr,
@@ -1025,7 +1027,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_combine_decode(R
                                                                    RoundConst rc)
 {
     __shared__ uint64_t lds[ENG::LDS_WORDS];
-    const uint32_t job = blockIdx.y;
+    const uint32_t job = gridDim.y - 1 - blockIdx.y;
     const uint64_t *first = jobs.first[job];
     combine_body<ENG, true, COMBINE_CONVERT>(lds, jobs.ct[job], [&](uint32_t j) { return first + (size_t)j * stride; },
                                   jobs.K[job], jobs.sk[job], false, (uint64_t *)nullptr, (float *)jobs.out[job],
