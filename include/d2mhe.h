@@ -178,7 +178,8 @@ size_t d2mhe_round_scratch_bytes(const d2mhe_ctx *ctx, uint32_t num_jobs, uint32
  * After the call the scratch holds, in this order, the fresh ciphertexts [J][C][2][L][N]
  * (job order), the aggregates [G][C][2][L][N] and the shares [J][C][L][N].
  * phase_events: NULL, or a HOST array of 5 hipEvent_t recorded on `stream` before the
- * first kernel and after the encrypt, sum, share and combine phases.                       */
+ * first kernel and after the encrypt, sum, share and combine phases; entries may be NULL
+ * (that event is skipped).                                                                  */
 d2mhe_status d2mhe_round(d2mhe_ctx *ctx, const d2mhe_round_desc *desc, void *scratch,
                          size_t scratch_bytes, void *const *phase_events, void *stream);
 /* The same for a single group: sk_shares, grads: HOST arrays of K device pointers in member

@@ -731,7 +731,7 @@ d2mhe_status run_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_co
     hipStream_t st = (hipStream_t)stream;
     const EngineOps *ops = engine_ops(ctx);
     hipEvent_t *ev = (hipEvent_t *)phase_events;
-    if (ev) D2_HIP(ctx, hipEventRecord(ev[0], st));
+    if (ev && ev[0]) D2_HIP(ctx, hipEventRecord(ev[0], st));
 
     // phase 1: every member of every group encodes and encrypts its gradient
     std::vector<uint32_t> group_of(J);
@@ -751,7 +751,7 @@ d2mhe_status run_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_co
         d2mhe_status s = ops->encrypt(ctx, true, jobs, n, d->ct_base, d->n_values, C, st);
         if (s != D2MHE_OK) return s;
     }
-    if (ev) D2_HIP(ctx, hipEventRecord(ev[1], st));
+    if (ev && ev[1]) D2_HIP(ctx, hipEventRecord(ev[1], st));
 
     // phase 2: homomorphic sum per group
     for (uint32_t g0 = 0; g0 < G; g0 += JOB_CHUNK) {
@@ -768,7 +768,7 @@ d2mhe_status run_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_co
                            ct_words, ctx->d_tabs, ctx->L, ctx->log2n, ct_words);
         D2_LAUNCHED(ctx);
     }
-    if (ev) D2_HIP(ctx, hipEventRecord(ev[2], st));
+    if (ev && ev[2]) D2_HIP(ctx, hipEventRecord(ev[2], st));
 
     if (!conv) {
         // phase 3: every member's decryption share of its group's aggregate
@@ -786,7 +786,7 @@ d2mhe_status run_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_co
             d2mhe_status s = ops->share(ctx, jobs, n, d->ct_base, C, st);
             if (s != D2MHE_OK) return s;
         }
-        if (ev) D2_HIP(ctx, hipEventRecord(ev[3], st));
+        if (ev && ev[3]) D2_HIP(ctx, hipEventRecord(ev[3], st));
 
         // phase 4: combine the shares, round, decode
         for (uint32_t g0 = 0; g0 < G; g0 += JOB_CHUNK) {
@@ -802,7 +802,7 @@ d2mhe_status run_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_co
             d2mhe_status s = ops->combine_decode(ctx, jobs, n, sh_words, C, d->n_values, st);
             if (s != D2MHE_OK) return s;
         }
-        if (ev) D2_HIP(ctx, hipEventRecord(ev[4], st));
+        if (ev && ev[4]) D2_HIP(ctx, hipEventRecord(ev[4], st));
         return D2MHE_OK;
     }
 
@@ -834,7 +834,7 @@ d2mhe_status run_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_co
         d2mhe_status s = ops->convert_share(ctx, jobs, n, d->ct_base, C, st);
         if (s != D2MHE_OK) return s;
     }
-    if (ev) D2_HIP(ctx, hipEventRecord(ev[3], st));
+    if (ev && ev[3]) D2_HIP(ctx, hipEventRecord(ev[3], st));
 
     // phase 4 (Convert): every receiver forms its ciphertext, decrypts with its own key, decodes
     for (uint32_t r0 = 0; r0 < R; r0 += CONV_CHUNK) {
@@ -853,7 +853,7 @@ d2mhe_status run_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_co
         d2mhe_status s = ops->convert_combine_decode(ctx, jobs, n, ct_words, C, d->n_values, st);
         if (s != D2MHE_OK) return s;
     }
-    if (ev) D2_HIP(ctx, hipEventRecord(ev[4], st));
+    if (ev && ev[4]) D2_HIP(ctx, hipEventRecord(ev[4], st));
     return D2MHE_OK;
 }
 
