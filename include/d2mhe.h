@@ -37,7 +37,11 @@
  * value floor(3w/2^32)-1; centred-binomial coefficient n = words 2(n&1), 2(n&1)+1 of block
  * n>>1, popcount(low eta bits) difference; uniform coefficient n = 128-bit block n mod q_i.
  * Domains: 1 secret share, 2 public-key error, 3 common random polynomial (per limb),
- * 4/5/6 mu/e0/e1 of Encrypt, 7 decryption-share error, 8 benchmark polynomials.
+ * 4/5/6 mu/e0/e1 of Encrypt, 7 decryption-share error, 8 benchmark polynomials;
+ * 0x10/0x11/0x12 a receiver's own secret key / uniform p1 (per limb) / key error,
+ * 0x13/0x14/0x15 mu/e0/e1 of a conversion share (party word = member | receiver << 16);
+ * 0x16 the mask M_k of a refresh share (block n mod t), 0x17/0x18 its e0/e1,
+ * 0x19 the common polynomial alpha of a refresh (per limb, party word 0).
  */
 #ifndef D2MHE_H
 #define D2MHE_H
