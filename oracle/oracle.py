@@ -44,7 +44,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        # D2MHE_ORACLE_LIBRARY: a build of this oracle from another source file (the test-suite points
+        # it at copies with a planted mistake to check that the pins notice)
+        _lib = C.CDLL(os.environ.get("D2MHE_ORACLE_LIBRARY") or build())
         u64, u32, i32, vp = C.c_uint64, C.c_uint32, C.c_int, C.c_void_p
         sz = C.c_size_t
         sig = {

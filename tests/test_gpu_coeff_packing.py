@@ -34,6 +34,17 @@ def test_encode_decode_coefficients(name):
     dres = torch.zeros(n, dtype=torch.float32, device=DEV)
     ctx.decode_coefficients(to_dev(anypt), C_, n, dres)
     assert np.array_equal(dres.cpu().numpy(), o.decode_coefficients(anypt, n))
+    # slot decoding of arbitrary plaintexts, and of one whose slots sit at the centring boundary
+    ctx.decode(to_dev(anypt), C_, n, dres)
+    assert np.array_equal(dres.cpu().numpy(), o.decode(anypt, n))
+    z = np.zeros((C_, N), dtype=np.uint64)
+    z[0, :5] = [(cfg.t - 1) // 2, (cfg.t + 1) // 2, cfg.t - 1, 1, (cfg.t - 1) // 2 - 1]
+    edge = np.stack([O.ntt_inverse(z[c], cfg.t, o.psi_t) for c in range(C_)])
+    ctx.decode(to_dev(edge), C_, n, dres)
+    got = dres.cpu().numpy()
+    assert np.array_equal(got, o.decode(edge, n))
+    half = (cfg.t - 1) // 2
+    assert list(got[:5] * np.float32(2.0 ** cfg.frac_bits)) == [half, -half, -1, 1, half - 1]
     # the slot encoding of the same values is its inverse transform modulo t
     dslots = dzeros(C_ * N)
     ctx.encode(to_dev(g), n, dslots, C_)

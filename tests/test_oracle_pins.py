@@ -624,6 +624,48 @@ def test_coefficient_packing_cross_check(orc):
     assert np.array_equal(sums[1], (fixed.astype(np.float32) * np.float32(0.25)))
 
 
+def test_decode_centres_at_the_boundary(orc):
+    """(t-1)/2 is the largest positive value and (t+1)/2 the most negative one, for slots and for coefficients."""
+    t, n = 193, 32
+    o = orc.Oracle(5, orc.find_primes(36, 5, 1), t, 21, 2, 1, SEED)
+    z = np.zeros(n, dtype=np.uint64)
+    z[:6] = [0, 1, (t - 1) // 2, (t + 1) // 2, t - 1, (t - 1) // 2 - 1]
+    expect = np.array([0, 1, 96, -96, -1, 95], dtype=np.float32) / np.float32(4)
+    assert np.array_equal(o.decode_coefficients(z[None], n)[:6], expect)
+    pt = orc.ntt_inverse(z, t, o.psi_t)                  # the polynomial with these slot values (textbook transform)
+    assert np.array_equal(o.decode(pt[None], n)[:6], expect)
+    assert np.all(o.decode(pt[None], n)[6:] == 0)
+
+
+def test_ciphertext_index_advances_within_a_call(orc):
+    """C ciphertexts in one call are C one-ciphertext calls at ct_base, ct_base + 1, ... (those are pinned against
+    the big-integer reference above), for every randomised step; equal plaintexts still give different ciphertexts."""
+    o, ref, qs = _toy(orc, 4, 36, 2, 97, 2, 3)
+    n, K, group, base, C_ = 16, 2, 3, 9, 3
+    keys = [o.keygen_share(k) for k in range(K)]
+    pk = o.aggregate_pk([k[1] for k in keys])
+    rsk, rpk, _, _ = o.receiver_keygen(1)
+    pt = np.tile(np.arange(n, dtype=np.uint64) % 97, (C_, 1))
+    ct = o.encrypt(pk, pt, 0, group, ct_base=base)
+    sh = o.partial_decrypt(keys[1][0], ct, 1, group, ct_base=base)
+    cv = o.convert_share(keys[1][0], rpk, ct, 1, 1, group, ct_base=base)
+    bs = [o.bootstrap_share(keys[k][0], ct, k, group, ct_base=base) for k in range(K)]
+    fresh = o.bootstrap_combine(ct, bs, group, ct_base=base)
+    for c in range(C_):
+        one = o.encrypt(pk, pt[c:c + 1], 0, group, ct_base=base + c)
+        assert np.array_equal(ct[c], one[0])
+        assert np.array_equal(sh[c], o.partial_decrypt(keys[1][0], one, 1, group, ct_base=base + c)[0])
+        assert np.array_equal(cv[c], o.convert_share(keys[1][0], rpk, one, 1, 1, group, ct_base=base + c)[0])
+        bs1 = [o.bootstrap_share(keys[k][0], one, k, group, ct_base=base + c) for k in range(K)]
+        for k in range(K):
+            assert np.array_equal(bs[k][c], bs1[k][0])
+        assert np.array_equal(fresh[c], o.bootstrap_combine(one, bs1, group, ct_base=base + c)[0])
+        assert np.array_equal(fresh[c, 1], o.bootstrap_alpha(group, base + c))
+        assert np.array_equal(fresh[c, 1], _residues(ref.bootstrap_alpha(group, base + c), qs))
+    for a, b in ((ct[0], ct[1]), (sh[0], sh[1]), (cv[0], cv[1]), (bs[0][0], bs[0][1]), (fresh[0, 1], fresh[1, 1])):
+        assert not np.array_equal(a, b)
+
+
 def test_fixed_point_error_bound(orc):
     o, _, _ = _toy(orc, 6, 36, 2, 65537, 1, 13)
     rng = np.random.default_rng(7)
