@@ -65,6 +65,22 @@ MUTANTS = [
     ("share_index_stuck", "ORC_DOM_DEC_E, party, group, ct_base + ci,", "ORC_DOM_DEC_E, party, group, ct_base,"),
     ("convert_index_stuck", "uint32_t index = ct_base + ci;\n        orc_sample_ternary(c->p.seed, ORC_DOM_CVT_U", "uint32_t index = ct_base;\n        orc_sample_ternary(c->p.seed, ORC_DOM_CVT_U"),
     ("refresh_index_stuck", "uint32_t index = ct_base + ci;\n        orc_sample_uniform(c->p.seed, ORC_DOM_BS_M", "uint32_t index = ct_base;\n        orc_sample_uniform(c->p.seed, ORC_DOM_BS_M"),
+    ("small_negative_lift", "return v >= 0 ? (uint64_t)v : q - (uint64_t)(-(int64_t)v); }", "return v >= 0 ? (uint64_t)v : q - 1 - (uint64_t)(-(int64_t)v); }"),
+    ("lambda_rounded_up", "        big_div_u64(&c->Lambda, p->t);\n", "        big_div_u64(&c->Lambda, p->t);\n        { big_t one_; big_set_u64(&one_, 1); big_add(&c->Lambda, &one_); }\n"),
+    ("clamp_ignores_group_size", "c->clamp = (int64_t)(((p->t - 1) / 2) / kmax);", "c->clamp = (int64_t)((p->t - 1) / 2);"),
+    ("crt_basis_includes_own_prime", "if (j != i) big_mul_u64(&c->Q_over_qi[i], p->q[j]);", "big_mul_u64(&c->Q_over_qi[i], p->q[j]);"),
+    ("encode_truncates", "float rf = isnan(v) ? 0.0f : rintf(v * scale);\n                if (rf > bound) rf = bound;\n                if (rf < -bound) rf = -bound;\n                r = (int64_t)rf;\n            }\n            z[j] =",
+     "float rf = isnan(v) ? 0.0f : truncf(v * scale);\n                if (rf > bound) rf = bound;\n                if (rf < -bound) rf = -bound;\n                r = (int64_t)rf;\n            }\n            z[j] ="),
+    ("encode_negative_off_by_one", "            z[j] = r >= 0 ? (uint64_t)r : t - (uint64_t)(-r);", "            z[j] = r >= 0 ? (uint64_t)r : t - 1 - (uint64_t)(-r);"),
+    ("encode_tail_not_zero", "            int64_t r = 0;\n            if (idx < n_values) {\n                float v = grad[idx];\n                float rf = isnan(v) ? 0.0f : rintf(v * scale);\n                if (rf > bound) rf = bound;\n                if (rf < -bound) rf = -bound;\n                r = (int64_t)rf;\n            }\n            z[j] =",
+     "            int64_t r = 1;\n            if (idx < n_values) {\n                float v = grad[idx];\n                float rf = isnan(v) ? 0.0f : rintf(v * scale);\n                if (rf > bound) rf = bound;\n                if (rf < -bound) rf = -bound;\n                r = (int64_t)rf;\n            }\n            z[j] ="),
+    ("coefficient_encode_upper_clamp_dropped", "            if (rf > bound) rf = bound;\n            if (rf < -bound) rf = -bound;\n            r = (int64_t)rf;\n        }\n        pt[idx] =",
+     "            if (rf < -bound) rf = -bound;\n            r = (int64_t)rf;\n        }\n        pt[idx] ="),
+    ("decode_scale_sign", "            out[idx] = ldexpf((float)v, -(int)c->p.frac_bits);\n        }\n    }\n    free(z);", "            out[idx] = ldexpf((float)v, (int)c->p.frac_bits);\n        }\n    }\n    free(z);"),
+    ("round_group_shares_of_a_fresh_ciphertext", "orc_partial_decrypt(c, sks[m], agg, 1, members[m], group, (uint32_t)ci,", "orc_partial_decrypt(c, sks[m], ct, 1, members[m], group, (uint32_t)ci,"),
+    # (orc_round_group returns decoded sums only, which do not depend on which randomness index it encrypts with)
+    ("single_key_decrypt_without_c0", "                y[(size_t)i * n + k] = addmod(y[(size_t)i * n + k], c0[(size_t)i * n + k], q);\n", "                (void)c0;\n"),
+    ("is_prime_without_the_squaring_loop", "        if (witness) return 0;\n", "        if (witness && r < 2) return 0;\n"),
     ("update_step_sign", "w[j] = avg - step;", "w[j] = avg + step;"),
     ("update_divides_by_k_plus_one", "volatile float inv_k = 1.0f / (float)K;", "volatile float inv_k = 1.0f / (float)(K + 1);"),
 ]
