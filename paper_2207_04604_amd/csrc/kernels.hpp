@@ -291,7 +291,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_forward(uint64_t *p
     typename ENG::Twiddles tw;
     ENG::template load_all<false, false>(tw, tid, tt.blk, tb.fwd);
     const size_t stride = (size_t)L << ENG::LOGN;        // words between members
-    uint64_t *p = polys + ((size_t)tt.m0 * L + tt.limb << ENG::LOGN) + ((size_t)tt.blk << ENG::LOGB);
+    uint64_t *p = polys + (((size_t)tt.m0 * L + tt.limb) << ENG::LOGN) + ((size_t)tt.blk << ENG::LOGB);
     uint64_t nx[E];
 #pragma unroll
     for (int k = 0; k < E; ++k) nx[k] = ld64(p, 8u * (uint32_t)tid, 8u * ENG::T * k);
@@ -325,7 +325,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_tail_inverse(uint64_t *p
     ENG::template load_all<true, false>(tw, tid, tt.blk, tb.inv);
     const typename A::Twid ninv = A::tw(tb.ninv), wn = A::tw(tb.wn);
     const size_t stride = (size_t)L << ENG::LOGN;
-    uint64_t *p = polys + ((size_t)tt.m0 * L + tt.limb << ENG::LOGN) + ((size_t)tt.blk << ENG::LOGB);
+    uint64_t *p = polys + (((size_t)tt.m0 * L + tt.limb) << ENG::LOGN) + ((size_t)tt.blk << ENG::LOGB);
     uint64_t nx[E];
 #pragma unroll
     for (int k = 0; k < E; ++k) nx[k] = ld64(p, 8u * (uint32_t)tid, 8u * ENG::T * k);
