@@ -6,7 +6,8 @@ import pytest
 import torch
 
 from paper_2207_04604_amd import binding as B
-from paper_2207_04604_amd.synth import CONFIGS
+from oracle import oracle as O
+from paper_2207_04604_amd.synth import CONFIGS, toy_config
 
 from gpu_util import DEV, Keys, dzeros, make_pair, to_dev, to_eval, to_host
 from test_gpu_parity import fixed_point_sum
@@ -211,4 +212,66 @@ def test_convert_argument_checks():
         ctx.decrypt(None, buf, 1, buf)
     assert ei.value.status == B.ERR_NULL
     ctx.convert_share(buf, buf, buf, 0, 1, 2, 0, 0, buf)        # C = 0: nothing to do
+    ctx.close()
+
+
+def test_rounds_with_more_groups_than_one_launch_takes():
+    """130 two-member groups over 131 parties: more jobs, groups, conversion shares and receivers than one
+    launch's table holds (112 / 112 / 80 / 80), so every phase of both rounds is split over several launches.
+    Every group's result against the fixed-point sum, sampled objects against the oracle."""
+    P, G = 131, 130
+    cfg = toy_config(10, O.find_primes(36, 10, 2), 12289, P, 1024 + 11, frac_bits=4)
+    o, ctx, perm = make_pair(cfg, max_group=2)
+    L, N, C_, n = o.L, o.N, cfg.C, cfg.n_values
+    rng = np.random.default_rng(130)
+    grads = [rng.normal(0, 20.0, n).astype(np.float32) for _ in range(P)]
+    groups = [[g, g + 1] for g in range(G)]
+    receivers = [[g + (g % 2)] for g in range(G)]                 # one of the two members
+    keys = Keys(o, ctx, perm, range(P), check=False)
+    rkeys = RecvKeys(o, ctx, perm, sorted({r[0] for r in receivers}))
+    pks = [keys.group_pk(g, perm, check=False) for g in groups]
+    dgr = [to_dev(g) for g in grads]
+    outs = [torch.zeros(n, dtype=torch.float32, device=DEV) for _ in groups]
+    desc = ctx.make_round(groups, [p[1] for p in pks], [keys.sk[k] for k in range(P)], dgr, outs, n, ct_base=5)
+    J = 2 * G
+    nbytes = ctx.round_scratch_bytes(J, G, n)
+    scratch = dzeros(nbytes // 8)
+    ctx.round(desc, scratch, nbytes)
+    torch.cuda.synchronize()
+    clamp = o.encode_clamp()
+    expects = [fixed_point_sum([grads[k] for k in g], cfg.frac_bits, clamp) for g in groups]
+    for gi in range(G):
+        assert np.array_equal(outs[gi].cpu().numpy(), expects[gi]), f"group {gi}"
+    LN = L * N
+    cts = scratch[:J * C_ * 2 * LN].view(J, C_, 2 * LN)
+    agg = scratch[J * C_ * 2 * LN:(J + G) * C_ * 2 * LN].view(G, C_, 2 * LN)
+    shares = scratch[(J + G) * C_ * 2 * LN:(J + G) * C_ * 2 * LN + J * C_ * LN].view(J, C_, LN)
+    for gi in (0, 55, 56, 111, 112, 129):                          # around the launch boundaries
+        opk = pks[gi][0]
+        octs = [o.encrypt(opk, o.encode(grads[k]), k, gi, ct_base=5) for k in groups[gi]]
+        oagg = o.add(octs[0], octs[1])
+        for m in range(2):
+            assert np.array_equal(to_host(cts[2 * gi + m], octs[m].shape), to_eval(o, perm, octs[m])), (gi, m)
+            osh = o.partial_decrypt(keys.osk[groups[gi][m]], oagg, groups[gi][m], gi, ct_base=5)
+            assert np.array_equal(to_host(shares[2 * gi + m], osh.shape), to_eval(o, perm, osh)), (gi, m)
+        assert np.array_equal(to_host(agg[gi], oagg.shape), to_eval(o, perm, oagg)), gi
+    del scratch
+    routs = [torch.zeros(n, dtype=torch.float32, device=DEV) for _ in range(G)]
+    conv = ctx.make_convert(desc, receivers, rkeys.pk, rkeys.sk, routs)
+    assert conv.num_shares == 2 * G
+    nbytes = ctx.round_convert_scratch_bytes(J, G, conv.num_shares, n)
+    scratch = dzeros(nbytes // 8)
+    ctx.round_convert(desc, conv, scratch, nbytes)
+    torch.cuda.synchronize()
+    for gi in range(G):
+        assert np.array_equal(routs[gi].cpu().numpy(), expects[gi]), f"receiver of group {gi}"
+    cshares = scratch[(J + G) * C_ * 2 * LN:(J + G + 2 * G) * C_ * 2 * LN].view(2 * G, C_, 2 * LN)
+    for gi in (39, 40, 79, 80, 129):
+        opk = pks[gi][0]
+        octs = [o.encrypt(opk, o.encode(grads[k]), k, gi, ct_base=5) for k in groups[gi]]
+        oagg = o.add(octs[0], octs[1])
+        r = receivers[gi][0]
+        for m in range(2):
+            osh = o.convert_share(keys.osk[groups[gi][m]], rkeys.opk[r], oagg, groups[gi][m], r, gi, ct_base=5)
+            assert np.array_equal(to_host(cshares[2 * gi + m], osh.shape), to_eval(o, perm, osh)), (gi, m)
     ctx.close()
