@@ -191,7 +191,9 @@ def main():
         "metric": "BFV gradient ciphertexts/sec (encrypt+aggregate+decrypt-share)",
         "value": value, "unit": "fresh ciphertexts/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u64" if arith != "f64" else "f64 (exact integers)", "data": "synthetic",
+        "dtype": "u64" if arith != "f64" else "f64",
+        "dtype_note": "residues below 2^44 are held as exact integers in doubles, wider ones as 64-bit integers",
+        "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={N}, L={L}, t={cfg.t}, P={P}, G={G}, K={cfg.max_group}, C={C_}, "
                                f"{cfg.n_values} floats/party", "fresh_ciphertexts": fresh,
                    "aggregated_ciphertexts": G * C_},
