@@ -545,7 +545,8 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
 {
     typedef typename ENG::A A;
     typedef typename A::elem elem;
-    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    __shared__ uint64_t lds[ENG::LDS_CHAIN_WORDS];
+    uint32_t turn = 0;      // staging uses buffer 0; the transforms then take the two buffers in turn
     uint32_t *lds32 = (uint32_t *)lds;
     constexpr int E = ENG::E;
     const int tid = threadIdx.x;
@@ -587,7 +588,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
         elem u[E];
 #pragma unroll
         for (int k = 0; k < E; ++k) u[k] = A::from_small(sbyte(opaque(smp[k]), 0), md);
-        ENG::forward(u, lds, tl, 0, tb.fwd, md);
+        ENG::forward_chained(u, lds, turn, tl, 0, tb.fwd, md);
         if (STASH) {
 #pragma unroll
             for (int k = 0; k < E; ++k) st64(stash, 8u * (uint32_t)tl, 8u * ENG::T * k, to_bits<A>(u[k]));
@@ -597,7 +598,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
         for (int k = 0; k < E; ++k)
             x[k] = A::add(A::mul(A::from_canon((uint64_t)opaque(m[k]), md), lam, md),
                           A::from_small(sbyte(opaque(smp[k]), 1), md));
-        ENG::forward(x, lds, opaque(tl), 0, tb.fwd, md);
+        ENG::forward_chained(x, lds, turn, opaque(tl), 0, tb.fwd, md);
         // the key values are requested in one batch (a load placed after a store of the previous
         // slot could not be moved in front of it)
         typename A::Twid kv[E];
@@ -611,7 +612,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
         }
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(opaque(smp[k]), 2), md);
-        ENG::forward(x, lds, opaque(tl), 0, tb.fwd, md);
+        ENG::forward_chained(x, lds, turn, opaque(tl), 0, tb.fwd, md);
 #pragma unroll
         for (int k = 0; k < E; ++k) kv[k] = A::key(p1, p1s, 8u * (uint32_t)tl, 8u * ENG::T * k);
 #pragma unroll
@@ -936,7 +937,8 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_share(ConvJobs j
 {
     typedef typename ENG::A A;
     typedef typename A::elem elem;
-    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    __shared__ uint64_t lds[ENG::LDS_CHAIN_WORDS];
+    uint32_t turn = 0;      // staging uses buffer 0; the transforms then take the two buffers in turn
     uint32_t *lds32 = (uint32_t *)lds;
     constexpr int E = ENG::E;
     const int tid = threadIdx.x;
@@ -962,7 +964,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_share(ConvJobs j
         elem u[E];
 #pragma unroll
         for (int k = 0; k < E; ++k) u[k] = A::from_small(sbyte(opaque(smp[k]), 0), md);
-        ENG::forward(u, lds, tl, 0, tb.fwd, md);
+        ENG::forward_chained(u, lds, turn, tl, 0, tb.fwd, md);
         if (STASH) {
 #pragma unroll
             for (int k = 0; k < E; ++k) st64(stash, 8u * (uint32_t)tl, 8u * ENG::T * k, to_bits<A>(u[k]));
@@ -970,7 +972,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_share(ConvJobs j
         elem x[E];
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(opaque(smp[k]), 1), md);
-        ENG::forward(x, lds, opaque(tl), 0, tb.fwd, md);
+        ENG::forward_chained(x, lds, turn, opaque(tl), 0, tb.fwd, md);
         {
             // h0: two products per slot, each reduced on its own
             typename A::Twid kv[E];
@@ -992,7 +994,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_share(ConvJobs j
         }
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(opaque(smp[k]), 2), md);
-        ENG::forward(x, lds, opaque(tl), 0, tb.fwd, md);
+        ENG::forward_chained(x, lds, turn, opaque(tl), 0, tb.fwd, md);
         {
             typename A::Twid kv[E];
 #pragma unroll
@@ -1071,7 +1073,8 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_bootstrap_share(ConvJobs
 {
     typedef typename ENG::A A;
     typedef typename A::elem elem;
-    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    __shared__ uint64_t lds[ENG::LDS_CHAIN_WORDS];
+    uint32_t turn = 0;      // staging uses buffer 0; the transforms then take the two buffers in turn
     uint32_t *lds32 = (uint32_t *)lds;
     constexpr int E = ENG::E;
     const int tid = threadIdx.x;
@@ -1115,7 +1118,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_bootstrap_share(ConvJobs
 #pragma unroll
         for (int k = 0; k < E; ++k)
             x[k] = A::add(A::from_canon(lm[k] ? q - lm[k] : 0, md), A::from_small(sbyte(opaque(ev[k]), 0), md));
-        ENG::forward(x, lds, tl, 0, tb.fwd, md);
+        ENG::forward_chained(x, lds, turn, tl, 0, tb.fwd, md);
         {
             typename A::Twid kv[E];
 #pragma unroll
@@ -1130,7 +1133,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_bootstrap_share(ConvJobs
 #pragma unroll
         for (int k = 0; k < E; ++k)
             x[k] = A::add(A::from_canon(lm[k], md), A::from_small(sbyte(opaque(ev[k]), 1), md));
-        ENG::forward(x, lds, opaque(tl), 0, tb.fwd, md);
+        ENG::forward_chained(x, lds, turn, opaque(tl), 0, tb.fwd, md);
         {
             typename A::Twid kv[E];
 #pragma unroll

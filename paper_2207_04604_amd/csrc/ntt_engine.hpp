@@ -66,6 +66,25 @@ struct Engine {
     static constexpr int NPASS = (LOGB + ELOG - 1) / ELOG;
     static constexpr int LDS_WORDS = NB + (NB >> ELOG);   // one pad word per E coefficients
     static constexpr int WAVES = 4;   // waves per SIMD the kernels are compiled for (<= 128 VGPRs)
+    // Kernels that run several forward transforms in a row give them two LDS buffers in turn where
+    // two fit next to the expected number of resident workgroups (160 KB per CU): the writer of an
+    // exchange then never meets a reader of the previous transform, which still works in the other
+    // buffer, and the workgroup barrier in front of the write goes away (one barrier per transform
+    // instead of two).  Transform n writes buffer n mod 2; its barrier between write and read is
+    // reached by every wave only after that wave has finished transform n - 1, hence before any wave
+    // starts writing for transform n + 1.
+    static constexpr bool PINGPONG = (size_t)LDS_WORDS * 8 * 2 * (T >= 1024 ? 1 : 2) <= 160 * 1024;
+    static constexpr int LDS_CHAIN_WORDS = (PINGPONG ? 2 : 1) * LDS_WORDS;
+    // the buffer of the next transform of a chain; `turn` starts at 0 when buffer 0 was used last
+    D2_DEV static uint64_t *next_buffer(uint64_t *lds, uint32_t &turn)
+    {
+        if constexpr (PINGPONG) {
+            turn ^= 1u;
+            return lds + turn * (uint32_t)LDS_WORDS;
+        } else {
+            return lds;
+        }
+    }
 
     static_assert(LOGB >= ELOG && LOGB <= LOGN, "bad engine shape");
 
@@ -235,14 +254,15 @@ struct Engine {
     static constexpr bool intra_wave() { return wbase(PF < PT ? PF : PT) <= 6; }
 
     // Hand the coefficients from the owners of pass PF to the owners of pass PT.
-    template <int PF, int PT>
+    // FRESH: no wave can still be reading this buffer (the first exchange of a chained transform, see PINGPONG).
+    template <int PF, int PT, bool FRESH = false>
     D2_DEV static void exchange(elem (&x)[E], uint64_t *lds, int tid)
     {
         constexpr int X = PF > PT ? PF : PT;
         constexpr bool INTRA = intra_wave<PF, PT>();
         uint64_t *wr = lds + slot_base<PF, X>(tid);
         const uint64_t *rd = lds + slot_base<PT, X>(tid);
-        if (INTRA) wave_sync(); else __syncthreads();      // earlier readers of these words are done
+        if (INTRA) wave_sync(); else if (!FRESH) __syncthreads();      // earlier readers of these words are done
 #pragma unroll
         for (int k = 0; k < E; ++k) wr[slot_off<PF, X>(k)] = to_bits<A>(x[k]);
         if (INTRA) wave_sync(); else __syncthreads();
@@ -250,7 +270,7 @@ struct Engine {
         for (int k = 0; k < E; ++k) x[k] = from_bits<A>(rd[slot_off<PT, X>(k)]);
     }
 
-    template <int P>
+    template <int P, bool FRESH = false>
     D2_DEV static void fwd_from(elem (&x)[E], const Twid (&w)[E], uint64_t *lds, int tid, uint32_t blk,
                                 const Tw *tw, const Mod &md)
     {
@@ -258,8 +278,8 @@ struct Engine {
             Twid wn[E];
             fwd_pass<P>(x, w, tid, blk, tw, md);
             load_tw<P + 1, false, true>(wn, tid, blk, tw);
-            exchange<P, P + 1>(x, lds, tid);
-            fwd_from<P + 1>(x, wn, lds, tid, blk, tw, md);
+            exchange<P, P + 1, FRESH && P == 0>(x, lds, tid);      // later exchanges meet this transform's own readers
+            fwd_from<P + 1, FRESH>(x, wn, lds, tid, blk, tw, md);
         } else {
             fwd_pass<P>(x, w, tid, blk, tw, md);
         }
@@ -291,6 +311,15 @@ struct Engine {
         fwd_from<0>(x, w, lds, tid, blk, tw, md);
     }
 
+    // The next forward transform of a chain (see PINGPONG); `lds` holds LDS_CHAIN_WORDS words.
+    D2_DEV static void forward_chained(elem (&x)[E], uint64_t *lds, uint32_t &turn, int tid, uint32_t blk, const Tw *tw,
+                                       const Mod &md)
+    {
+        Twid w[E];
+        load_tw<0, false, true>(w, tid, blk, tw);
+        fwd_from<0, PINGPONG>(x, w, next_buffer(lds, turn), tid, blk, tw, md);
+    }
+
     // All twiddles of one transform, for callers that run several transforms with the same table and
     // block id: fetched once, they stay in registers (scalar registers for the uniform passes).
     // Only for shapes whose passes all take their twiddles as a set.
@@ -307,15 +336,20 @@ struct Engine {
         if constexpr (P + 1 < NPASS) load_all<INV, FOLD, P + 1>(t, tid, blk, tw);
     }
 
-    template <int P = 0>
+    template <int P = 0, bool FRESH = false>
     D2_DEV static void forward(elem (&x)[E], uint64_t *lds, int tid, const Twiddles &t, const Mod &md)
     {
         static_assert(ahead<P>(), "shape loads twiddles stage by stage");
         fwd_pass<P>(x, t.w[P], tid, 0, nullptr, md);
         if constexpr (P + 1 < NPASS) {
-            exchange<P, P + 1>(x, lds, tid);
-            forward<P + 1>(x, lds, tid, t, md);
+            exchange<P, P + 1, FRESH && P == 0>(x, lds, tid);
+            forward<P + 1, FRESH>(x, lds, tid, t, md);
         }
+    }
+    D2_DEV static void forward_chained(elem (&x)[E], uint64_t *lds, uint32_t &turn, int tid, const Twiddles &t,
+                                       const Mod &md)
+    {
+        forward<0, PINGPONG>(x, next_buffer(lds, turn), tid, t, md);
     }
 
     template <bool FOLD, int P = NPASS - 1>
