@@ -631,7 +631,8 @@ template <class ENG>
 __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_share(ShareJobs jobs, uint32_t ct_base, const LimbTab *tabs, RoundConst rc)
 {
     typedef typename ENG::A A;
-    __shared__ uint64_t lds[ENG::LDS_WORDS];
+    __shared__ uint64_t lds[ENG::LDS_CHAIN_WORDS];
+    uint32_t turn = 0;
     uint32_t *lds32 = (uint32_t *)lds;
     constexpr int E = ENG::E;
     const int tid = threadIdx.x;
@@ -653,7 +654,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_share(ShareJobs jobs, ui
         typename A::elem x[E];
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = A::from_small(opaque(e[k]), md);
-        ENG::forward(x, lds, tl, 0, tb.fwd, md);
+        ENG::forward_chained(x, lds, turn, tl, 0, tb.fwd, md);
         typename A::Twid kv[E];
         uint64_t cv[E];
 #pragma unroll
