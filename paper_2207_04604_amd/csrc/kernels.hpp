@@ -386,6 +386,7 @@ D2_DEV int32_t sbyte(uint32_t w, int i) { return (int32_t)(int8_t)(w >> (8 * i))
 // ciphertext index c in registers in pass-0 (natural) ownership, values in [0, t).
 // With rc.coeff_packing the values are the coefficients themselves (an addition-only workload
 // never needs the slot structure): no transform on either side.
+// `lds` must not have been used by the workgroup yet (no wave may still be reading it).
 // -------------------------------------------------------------------------------------
 template <class ENG>
 D2_DEV void encode_to_regs(uint32_t (&m)[ENG::E], uint64_t *lds, int tid, const float *grad, uint64_t first,
@@ -408,7 +409,7 @@ D2_DEV void encode_to_regs(uint32_t (&m)[ENG::E], uint64_t *lds, int tid, const 
         for (int k = 0; k < ENG::E; ++k) m[k] = (uint32_t)fixed(first + (uint64_t)ENG::coef_pos(k, tid));
         return;
     }
-    __syncthreads();
+    // (no barrier in front of these writes: the callers have not used this buffer before)
     for (int j = tid; j < ENG::NB; j += ENG::T) lds[ENG::phys(j)] = fixed(first + (uint64_t)j);
     __syncthreads();
     // slot j is the evaluation xhat[j], which the engine keeps at block index bitrev(j)
@@ -546,7 +547,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
     typedef typename ENG::A A;
     typedef typename A::elem elem;
     __shared__ uint64_t lds[ENG::LDS_CHAIN_WORDS];
-    uint32_t turn = 0;      // staging uses buffer 0; the transforms then take the two buffers in turn
+    uint32_t turn = 0;      // the buffer used last; the transforms take the two buffers in turn
     uint32_t *lds32 = (uint32_t *)lds;
     constexpr int E = ENG::E;
     const int tid = threadIdx.x;
@@ -556,6 +557,14 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
     const size_t LN = (size_t)L * ENG::NB;
     uint64_t *out = jobs.out[job] + (size_t)c * 2 * LN;
 
+    // With two buffers the samples are staged in the second one, next to the encoding in the first:
+    // one barrier then makes them visible and also ends the encoding's reads of the first buffer,
+    // which the first transform of the chain takes.
+    uint32_t *stage = ENG::PINGPONG ? lds32 + 2 * ENG::LDS_WORDS : lds32;
+    if (ENG::PINGPONG) {
+        stage_encrypt_samples<ENG>(stage, tid, DOM_ENC_U, party, group, ct_base + c, rc);
+        turn = 1;
+    }
     uint32_t m[E];
     if (FROM_FLOAT) {
         encode_to_regs<ENG>(m, lds, tid, (const float *)jobs.src[job], (uint64_t)c * ENG::NB, n_values, load_tab(tabs, L), rc);
@@ -565,11 +574,13 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
         for (int k = 0; k < E; ++k) m[k] = (uint32_t)pt[ENG::coef_pos(k, tid)];
     }
     uint32_t smp[E];
-    __syncthreads();
-    stage_encrypt_samples<ENG>(lds32, tid, DOM_ENC_U, party, group, ct_base + c, rc);
+    if (!ENG::PINGPONG) {
+        __syncthreads();
+        stage_encrypt_samples<ENG>(stage, tid, DOM_ENC_U, party, group, ct_base + c, rc);
+    }
     __syncthreads();
 #pragma unroll
-    for (int k = 0; k < E; ++k) smp[k] = lds32[ENG::coef_pos(k, tid)];
+    for (int k = 0; k < E; ++k) smp[k] = stage[ENG::coef_pos(k, tid)];
 
     for (uint32_t limb = 0; limb < L; ++limb) {
         const LimbTab tb = load_tab(tabs, limb);
