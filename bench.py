@@ -138,21 +138,42 @@ def main():
             e.record(stream)                      # creates the underlying hipEvent_t
         return evs
 
+    def time_rounds(run, steps):
+        """The secondary legs: ms per round from `steps` rounds without events (after a short warm-up),
+        and the phase split from up to 20 further rounds with an event after every phase."""
+        for _ in range(min(args.warmup, 10)):
+            run(None)
+        torch.cuda.synchronize()
+        t_0 = time.perf_counter()
+        for _ in range(steps):
+            run(None)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t_0) * 1e3 / steps
+        n_ev = max(1, min(steps, 20))
+        evs = [new_events() for _ in range(n_ev)]
+        torch.cuda.synchronize()
+        for i in range(n_ev):
+            run([e.cuda_event for e in evs[i]])
+        torch.cuda.synchronize()
+        return ms, [sum(e[i].elapsed_time(e[i + 1]) for e in evs) / n_ev for i in range(4)]
+
     for _ in range(args.warmup):
         ctx.round(desc, scratch, nbytes, None, sptr)
     torch.cuda.synchronize()
-    # the timed region records two events per step, around the dominant kernel's phase; the
-    # phase split comes from a few more (untimed) steps with all five events
-    step_events = [new_events()[:2] for _ in range(args.steps)]
+    # the timed region records two events around the dominant kernel's launch on every EVENT_EVERY-th
+    # step (an event costs a few microseconds of idle GPU); the phase split comes from a few more
+    # (untimed) steps with all five events
+    EVENT_EVERY = 8
+    step_events = {i: new_events()[:2] for i in range(0, args.steps, EVENT_EVERY)}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        ctx.round(desc, scratch, nbytes, [step_events[i][0].cuda_event, step_events[i][1].cuda_event, None, None, None],
-                  sptr)
+        ev = step_events.get(i)
+        ctx.round(desc, scratch, nbytes, [ev[0].cuda_event, ev[1].cuda_event, None, None, None] if ev else None, sptr)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    enc_phase_ms = sum(ev[0].elapsed_time(ev[1]) for ev in step_events) / args.steps
+    enc_phase_ms = sum(ev[0].elapsed_time(ev[1]) for ev in step_events.values()) / len(step_events)
     nph = max(1, min(args.steps, 20))
     phase_events = [new_events() for _ in range(nph)]
     torch.cuda.synchronize()
@@ -203,7 +224,8 @@ def main():
                   "create_ms": t_create, "keys_ms": setup_ms},
         "phase_ms": {"encode_encrypt": phase_ms[0], "aggregate": phase_ms[1], "shares": phase_ms[2],
                      "combine_decode": phase_ms[3]},
-        "phase_ms_from": f"{nph} further steps with an event after every phase (the timed steps record two events)",
+        "phase_ms_from": f"{nph} further steps with an event after every phase (of the timed steps every {EVENT_EVERY}th "
+                         "records two events, around the dominant kernel)",
         "round_algorithmic": {"GB": round_bytes / 1e9, "GB_per_s": round_bytes / 1e9 / (ms_per_step * 1e-3),
                               "frac_hbm_peak": round_bytes / 1e9 / (ms_per_step * 1e-3) / HBM_PEAK_GBS,
                               "butterfly_Tops_per_s": round_bf * OPB / (ms_per_step * 1e-3) / 1e12,
@@ -222,20 +244,10 @@ def main():
     # addition-only workload does not need the slot structure, so both transforms modulo t go away
     if not args.no_coeff:
         pdesc = ctx.make_round(groups, pks, sks, grads, outs, cfg.n_values, packing=1)
-        psteps = max(1, min(args.steps, 50))
+        psteps = max(1, min(args.steps, 100))
         for o_ in outs:
             o_.zero_()
-        for _ in range(min(args.warmup, 2)):
-            ctx.round(pdesc, scratch, nbytes, None, sptr)
-        torch.cuda.synchronize()
-        pev = [new_events() for _ in range(psteps)]
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(psteps):
-            ctx.round(pdesc, scratch, nbytes, [e.cuda_event for e in pev[i]], sptr)
-        torch.cuda.synchronize()
-        pms = (time.perf_counter() - t0) * 1e3 / psteps
-        pphase = [sum(ev[i].elapsed_time(ev[i + 1]) for ev in pev) / psteps for i in range(4)]
+        pms, pphase = time_rounds(lambda ev: ctx.round(pdesc, scratch, nbytes, ev, sptr), psteps)
         for gi in (0, G - 1):
             acc = np.zeros(cfg.n_values, dtype=np.int64)
             for k in groups[gi]:
@@ -338,18 +350,8 @@ def main():
         cbytes = ctx.round_convert_scratch_bytes(J, G, conv.num_shares, cfg.n_values)
         del scratch
         cscratch = dz(cbytes // 8)
-        csteps = max(1, min(args.steps, 50))
-        for _ in range(min(args.warmup, 2)):
-            ctx.round_convert(desc, conv, cscratch, cbytes, None, sptr)
-        torch.cuda.synchronize()
-        cev = [new_events() for _ in range(csteps)]
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(csteps):
-            ctx.round_convert(desc, conv, cscratch, cbytes, [e.cuda_event for e in cev[i]], sptr)
-        torch.cuda.synchronize()
-        cms = (time.perf_counter() - t0) * 1e3 / csteps
-        cphase = [sum(ev[i].elapsed_time(ev[i + 1]) for ev in cev) / csteps for i in range(4)]
+        csteps = max(1, min(args.steps, 100))
+        cms, cphase = time_rounds(lambda ev: ctx.round_convert(desc, conv, cscratch, cbytes, ev, sptr), csteps)
         ri = 0
         for gi in range(G):
             for _ in receivers[gi]:
