@@ -194,6 +194,22 @@ d2mhe_status d2mhe_round_group(d2mhe_ctx *ctx, const uint64_t *pk,
                                uint64_t n_values, float *out_sum, void *scratch,
                                size_t scratch_bytes, void *stream);
 
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): d2mhe_round_group with the
+ * scratch in an array of D2MHE_STATIC_SCRATCH_BYTES that the library itself holds on every GPU it
+ * runs on, until the process ends.  The call allocates nothing, on the device or on the host, and
+ * gives the same out_sum as d2mhe_round_group.  A round that needs more scratch than the array holds
+ * (d2mhe_round_scratch_bytes(ctx, K, 1, n_values) > D2MHE_STATIC_SCRATCH_BYTES) is refused with
+ * D2MHE_ERR_WORKSPACE before anything is launched.  All calls on one GPU share that GPU's array (it
+ * keeps the last call's ciphertexts, aggregate and shares; every word a call reads it has written
+ * itself, so nothing needs clearing): calls that overlap in time on one GPU race, on any streams.
+ * The array's device address is looked up in d2mhe_create (and on a first call on another device). */
+#define D2MHE_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+d2mhe_status d2mhe_round_group_static(d2mhe_ctx *ctx, const uint64_t *pk,
+                                      const uint64_t *const *sk_shares, const float *const *grads,
+                                      const uint32_t *members, uint32_t K, uint32_t group,
+                                      uint64_t n_values, float *out_sum, void *stream);
+
 /* ---- the float step of one training iteration (Alg. 2 lines 9-10) ---------------------------- */
 /* w[j] = sum[j] * (1/K) - gamma * grad[j] in float32, each operation rounded on its own:
  * the average over a closed neighbourhood of K nodes from the decoded sum (the weights 1/K of the

@@ -15,13 +15,14 @@ LIB_PATH = os.environ.get("D2MHE_LIBRARY", os.path.join(_HERE, "libd2mhe.so"))
 
 OK = 0
 ERR_BAD_PARAMS, ERR_NULL, ERR_ALIGN, ERR_RANGE, ERR_WORKSPACE, ERR_HIP, ERR_UNIMPLEMENTED = range(-1, -8, -1)
+STATIC_SCRATCH_BYTES = 64 << 20          # D2MHE_STATIC_SCRATCH_BYTES of the header
 
 SYMBOLS = [
     "d2mhe_workspace_bytes", "d2mhe_create", "d2mhe_destroy", "d2mhe_strerror", "d2mhe_last_hip_error",
     "d2mhe_ntt_index_map", "d2mhe_root", "d2mhe_ntt_forward", "d2mhe_ntt_inverse", "d2mhe_bench_polys",
     "d2mhe_keygen_share", "d2mhe_aggregate_pk", "d2mhe_encode", "d2mhe_encrypt", "d2mhe_add",
     "d2mhe_partial_decrypt", "d2mhe_combine", "d2mhe_decode", "d2mhe_round_scratch_bytes",
-    "d2mhe_round", "d2mhe_round_group",
+    "d2mhe_round", "d2mhe_round_group", "d2mhe_round_group_static",
     "d2mhe_receiver_keygen", "d2mhe_convert_share", "d2mhe_convert_combine", "d2mhe_decrypt",
     "d2mhe_round_convert_scratch_bytes", "d2mhe_round_convert",
     "d2mhe_bootstrap_alpha", "d2mhe_bootstrap_share", "d2mhe_bootstrap_combine",
@@ -91,6 +92,7 @@ def lib():
         "d2mhe_round_scratch_bytes": (sz, [vp, u32, u32, u64]),
         "d2mhe_round": (i32, [vp, C.POINTER(RoundDesc), vp, sz, vp, vp]),
         "d2mhe_round_group": (i32, [vp, vp, vp, vp, vp, u32, u32, u64, vp, vp, sz, vp]),
+        "d2mhe_round_group_static": (i32, [vp, vp, vp, vp, vp, u32, u32, u64, vp, vp]),
         "d2mhe_receiver_keygen": (i32, [vp, u32, vp, vp, vp]),
         "d2mhe_convert_share": (i32, [vp, vp, vp, vp, u32, u32, u32, u32, u32, vp, vp]),
         "d2mhe_convert_combine": (i32, [vp, vp, vp, u32, u32, vp, vp]),
@@ -337,3 +339,10 @@ class Context:
         _check(lib().d2mhe_round_group(self._h, _ptr(pk), _ptr_table(sk_shares), _ptr_table(grads), ids,
                                        len(members), group, n_values, _ptr(out_sum), _ptr(scratch),
                                        scratch_bytes, stream), "d2mhe_round_group")
+
+    def round_group_static(self, pk, sk_shares, grads, members, group, n_values, out_sum, stream=None):
+        """round_group on the library's own scratch array (nothing is allocated)."""
+        ids = (C.c_uint32 * len(members))(*[int(m) for m in members])
+        _check(lib().d2mhe_round_group_static(self._h, _ptr(pk), _ptr_table(sk_shares), _ptr_table(grads), ids,
+                                              len(members), group, n_values, _ptr(out_sum), stream),
+               "d2mhe_round_group_static")

@@ -2,6 +2,7 @@
 // host-side table construction and kernel launches.  No device memory is allocated here.
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -171,6 +172,38 @@ d2mhe_status launch_ntt(d2mhe_ctx *ctx, uint64_t *polys, uint32_t B, bool forwar
 
 }  // namespace
 
+// ---- scratch memory of d2mhe_round_group_static ------------------------------------------------
+// A device array of the library's own, for callers that may not allocate.  In host code the name
+// of a __device__ array is only a stand-in for the symbol, never a device address: its address on
+// the current device comes from hipGetSymbolAddress, once per device (every device holds its own
+// copy of the array), and only that pointer is ever handed to a kernel or a runtime call.
+namespace {
+
+static __device__ __align__(256) uint64_t static_scratch[D2MHE_STATIC_SCRATCH_BYTES / sizeof(uint64_t)];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_static_lock;
+uint64_t *g_static_ptr[MAX_DEVICES];      // address of static_scratch on device i, null until looked up
+
+// Address of the array on the current device (looked up on first use; no allocation).
+d2mhe_status static_scratch_ptr(d2mhe_ctx *ctx, uint64_t **out)
+{
+    int dev = -1;
+    D2_HIP(ctx, hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return D2MHE_ERR_RANGE;
+    std::lock_guard<std::mutex> hold(g_static_lock);
+    if (!g_static_ptr[dev]) {
+        void *p = nullptr;
+        D2_HIP(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch)));
+        if (!p) return D2MHE_ERR_HIP;
+        g_static_ptr[dev] = (uint64_t *)p;
+    }
+    *out = g_static_ptr[dev];
+    return D2MHE_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 const char *d2mhe_strerror(d2mhe_status s)
@@ -315,6 +348,13 @@ d2mhe_status d2mhe_create(const d2mhe_params *p, void *dev_workspace, size_t byt
             delete ctx;
             return s;
         }
+    }
+    // d2mhe_round_group_static's scratch array: look its address up now, with this device current
+    uint64_t *own_scratch = nullptr;
+    const d2mhe_status ss = static_scratch_ptr(ctx, &own_scratch);
+    if (ss != D2MHE_OK) {
+        delete ctx;
+        return ss;
     }
     *out = ctx;
     return D2MHE_OK;
@@ -937,6 +977,81 @@ d2mhe_status d2mhe_round_group(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_
     d.ct_base = 0;
     d.packing = 0;
     return d2mhe_round(ctx, &d, scratch, scratch_bytes, nullptr, stream);
+}
+
+// d2mhe_round_group for callers that may not allocate: the same four launches on the library's own
+// scratch array.  Nothing here touches the heap or the device allocator: the job tables are on the
+// stack (K <= 64 fits one launch per phase) and travel in the kernel arguments.
+d2mhe_status d2mhe_round_group_static(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_t *const *sk_shares,
+                                      const float *const *grads, const uint32_t *members, uint32_t K,
+                                      uint32_t group, uint64_t n_values, float *out_sum, void *stream)
+{
+    D2_NEED_SCHEME(ctx);
+    if (!pk || !sk_shares || !grads || !members || !out_sum) return D2MHE_ERR_NULL;
+    if (K == 0 || K > (uint32_t)MAX_GROUP || K > ctx->max_group || group > 0xffffu) return D2MHE_ERR_RANGE;
+    static_assert(MAX_GROUP <= JOB_CHUNK, "a group must fit one launch");
+    if (misaligned(pk) || misaligned(out_sum)) return D2MHE_ERR_ALIGN;
+    for (uint32_t k = 0; k < K; ++k) {
+        if (members[k] > 0xffffu) return D2MHE_ERR_RANGE;
+        if (!sk_shares[k] || !grads[k]) return D2MHE_ERR_NULL;
+        if (misaligned(sk_shares[k]) || misaligned(grads[k])) return D2MHE_ERR_ALIGN;
+    }
+    if (n_values == 0) return D2MHE_OK;
+    const uint64_t C64 = (n_values + ctx->N - 1) / ctx->N;
+    if (C64 > 0x7fffffffull) return D2MHE_ERR_RANGE;
+    const uint32_t C = (uint32_t)C64;
+    // the limit: the scratch of this round must fit the array
+    const size_t LN = (size_t)ctx->L * ctx->N;
+    if (C64 > D2MHE_STATIC_SCRATCH_BYTES / sizeof(uint64_t) / ((size_t)(3 * K + 2) * LN)) return D2MHE_ERR_WORKSPACE;
+    uint64_t *base = nullptr;
+    const d2mhe_status ps = static_scratch_ptr(ctx, &base);       // the device address, never the array's name
+    if (ps != D2MHE_OK) return ps;
+
+    const size_t ct_words = (size_t)C * 2 * LN, sh_words = (size_t)C * LN;
+    uint64_t *cts = base, *agg = cts + (size_t)K * ct_words, *shares = agg + ct_words;
+    hipStream_t st = (hipStream_t)stream;
+    const EngineOps *ops = engine_ops(ctx);
+    d2mhe_ctx local = *ctx;                  // slot packing, whatever a concurrent call sets in its own copy
+    local.rc.coeff_packing = 0;
+
+    EncJobs enc;
+    ShareJobs shr;
+    for (uint32_t k = 0; k < K; ++k) {
+        enc.src[k] = grads[k];
+        enc.pk[k] = pk;
+        enc.out[k] = cts + (size_t)k * ct_words;
+        enc.party[k] = shr.party[k] = members[k];
+        enc.group[k] = shr.group[k] = group;
+        shr.sk[k] = sk_shares[k];
+        shr.ct[k] = agg;
+        shr.out[k] = shares + (size_t)k * sh_words;
+    }
+    d2mhe_status s = ops->encrypt(&local, true, enc, K, 0, n_values, C, st);
+    if (s == D2MHE_OK) {
+        GroupJobs sum;
+        sum.first[0] = cts;
+        sum.ct[0] = nullptr;
+        sum.out[0] = agg;
+        sum.K[0] = K;
+        hipLaunchKernelGGL(k_sum_groups, dim3((unsigned)((ct_words / 2 + 255) / 256), 1), dim3(256), 0, st, sum,
+                           ct_words, ctx->d_tabs, ctx->L, ctx->log2n, ct_words);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) {
+            local.last_hip = (int)e;
+            s = D2MHE_ERR_HIP;
+        }
+    }
+    if (s == D2MHE_OK) s = ops->share(&local, shr, K, 0, C, st);
+    if (s == D2MHE_OK) {
+        GroupJobs cmb;
+        cmb.first[0] = shares;
+        cmb.ct[0] = agg;
+        cmb.out[0] = out_sum;
+        cmb.K[0] = K;
+        s = ops->combine_decode(&local, cmb, 1, sh_words, C, n_values, st);
+    }
+    ctx->last_hip = local.last_hip;
+    return s;
 }
 
 }  // extern "C"
