@@ -514,7 +514,9 @@ int orc_encode(const orc_ctx *c, const float *grad, uint64_t n_values, uint64_t 
     uint64_t t = c->p.t;
     if (!t || n_values > (uint64_t)C * n) return -1;
     float scale = ldexpf(1.0f, (int)c->p.frac_bits);
-    float bound = (float)c->clamp;
+    /* the clamp is applied to the rounded value as an exact comparison (in double, which holds
+     * every float and every bound below 2^53): a bound above 2^24 need not be a float32          */
+    double bound = (double)c->clamp;
     for (uint32_t ci = 0; ci < C; ++ci) {
         uint64_t *z = pt + (size_t)ci * n;
         for (size_t j = 0; j < n; ++j) {
@@ -522,7 +524,7 @@ int orc_encode(const orc_ctx *c, const float *grad, uint64_t n_values, uint64_t 
             int64_t r = 0;
             if (idx < n_values) {
                 float v = grad[idx];
-                float rf = isnan(v) ? 0.0f : rintf(v * scale);
+                double rf = isnan(v) ? 0.0 : (double)rintf(v * scale);
                 if (rf > bound) rf = bound;
                 if (rf < -bound) rf = -bound;
                 r = (int64_t)rf;
@@ -562,12 +564,12 @@ int orc_encode_coefficients(const orc_ctx *c, const float *grad, uint64_t n_valu
     uint64_t t = c->p.t;
     if (!t || n_values > (uint64_t)C * n) return -1;
     float scale = ldexpf(1.0f, (int)c->p.frac_bits);
-    float bound = (float)c->clamp;
+    double bound = (double)c->clamp;      /* exact comparison, as in orc_encode */
     for (uint64_t idx = 0; idx < (uint64_t)C * n; ++idx) {
         int64_t r = 0;
         if (idx < n_values) {
             float v = grad[idx];
-            float rf = isnan(v) ? 0.0f : rintf(v * scale);
+            double rf = isnan(v) ? 0.0 : (double)rintf(v * scale);
             if (rf > bound) rf = bound;
             if (rf < -bound) rf = -bound;
             r = (int64_t)rf;

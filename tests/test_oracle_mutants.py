@@ -69,11 +69,11 @@ MUTANTS = [
     ("lambda_rounded_up", "        big_div_u64(&c->Lambda, p->t);\n", "        big_div_u64(&c->Lambda, p->t);\n        { big_t one_; big_set_u64(&one_, 1); big_add(&c->Lambda, &one_); }\n"),
     ("clamp_ignores_group_size", "c->clamp = (int64_t)(((p->t - 1) / 2) / kmax);", "c->clamp = (int64_t)((p->t - 1) / 2);"),
     ("crt_basis_includes_own_prime", "if (j != i) big_mul_u64(&c->Q_over_qi[i], p->q[j]);", "big_mul_u64(&c->Q_over_qi[i], p->q[j]);"),
-    ("encode_truncates", "float rf = isnan(v) ? 0.0f : rintf(v * scale);\n                if (rf > bound) rf = bound;\n                if (rf < -bound) rf = -bound;\n                r = (int64_t)rf;\n            }\n            z[j] =",
-     "float rf = isnan(v) ? 0.0f : truncf(v * scale);\n                if (rf > bound) rf = bound;\n                if (rf < -bound) rf = -bound;\n                r = (int64_t)rf;\n            }\n            z[j] ="),
+    ("encode_truncates", "double rf = isnan(v) ? 0.0 : (double)rintf(v * scale);\n                if (rf > bound) rf = bound;\n                if (rf < -bound) rf = -bound;\n                r = (int64_t)rf;\n            }\n            z[j] =",
+     "double rf = isnan(v) ? 0.0 : (double)truncf(v * scale);\n                if (rf > bound) rf = bound;\n                if (rf < -bound) rf = -bound;\n                r = (int64_t)rf;\n            }\n            z[j] ="),
     ("encode_negative_off_by_one", "            z[j] = r >= 0 ? (uint64_t)r : t - (uint64_t)(-r);", "            z[j] = r >= 0 ? (uint64_t)r : t - 1 - (uint64_t)(-r);"),
-    ("encode_tail_not_zero", "            int64_t r = 0;\n            if (idx < n_values) {\n                float v = grad[idx];\n                float rf = isnan(v) ? 0.0f : rintf(v * scale);\n                if (rf > bound) rf = bound;\n                if (rf < -bound) rf = -bound;\n                r = (int64_t)rf;\n            }\n            z[j] =",
-     "            int64_t r = 1;\n            if (idx < n_values) {\n                float v = grad[idx];\n                float rf = isnan(v) ? 0.0f : rintf(v * scale);\n                if (rf > bound) rf = bound;\n                if (rf < -bound) rf = -bound;\n                r = (int64_t)rf;\n            }\n            z[j] ="),
+    ("encode_tail_not_zero", "            int64_t r = 0;\n            if (idx < n_values) {\n                float v = grad[idx];\n                double rf = isnan(v) ? 0.0 : (double)rintf(v * scale);\n                if (rf > bound) rf = bound;\n                if (rf < -bound) rf = -bound;\n                r = (int64_t)rf;\n            }\n            z[j] =",
+     "            int64_t r = 1;\n            if (idx < n_values) {\n                float v = grad[idx];\n                double rf = isnan(v) ? 0.0 : (double)rintf(v * scale);\n                if (rf > bound) rf = bound;\n                if (rf < -bound) rf = -bound;\n                r = (int64_t)rf;\n            }\n            z[j] ="),
     ("coefficient_encode_upper_clamp_dropped", "            if (rf > bound) rf = bound;\n            if (rf < -bound) rf = -bound;\n            r = (int64_t)rf;\n        }\n        pt[idx] =",
      "            if (rf < -bound) rf = -bound;\n            r = (int64_t)rf;\n        }\n        pt[idx] ="),
     ("decode_scale_sign", "            out[idx] = ldexpf((float)v, -(int)c->p.frac_bits);\n        }\n    }\n    free(z);", "            out[idx] = ldexpf((float)v, (int)c->p.frac_bits);\n        }\n    }\n    free(z);"),
@@ -81,6 +81,16 @@ MUTANTS = [
     # (orc_round_group returns decoded sums only, which do not depend on which randomness index it encrypts with)
     ("single_key_decrypt_without_c0", "                y[(size_t)i * n + k] = addmod(y[(size_t)i * n + k], c0[(size_t)i * n + k], q);\n", "                (void)c0;\n"),
     ("is_prime_without_the_squaring_loop", "        if (witness) return 0;\n", "        if (witness && r < 2) return 0;\n"),
+    ("batch_forward_uses_limb_0_everywhere", "orc_ntt_forward(polys + (size_t)idx * c->n, c->n, c->p.q[idx % L], c->psi[idx % L]);",
+     "orc_ntt_forward(polys + (size_t)idx * c->n, c->n, c->p.q[0], c->psi[0]);"),
+    ("batch_inverse_root_of_wrong_limb", "orc_ntt_inverse(polys + (size_t)idx * c->n, c->n, c->p.q[idx % L], c->psi[idx % L]);",
+     "orc_ntt_inverse(polys + (size_t)idx * c->n, c->n, c->p.q[idx % L], c->psi[(idx + 1) % L]);"),
+    ("bench_polys_batch_and_limb_swapped", "orc_sample_uniform(c->p.seed, ORC_DOM_BENCH, i, 0, 0, b, c->p.q[i], c->n,",
+     "orc_sample_uniform(c->p.seed, ORC_DOM_BENCH, b, 0, 0, i, c->p.q[i], c->n,"),
+    ("clamp_bound_rounded_to_float32", "    double bound = (double)c->clamp;\n    for (uint32_t ci = 0; ci < C; ++ci) {",
+     "    double bound = (double)(float)c->clamp;\n    for (uint32_t ci = 0; ci < C; ++ci) {"),
+    ("coefficient_clamp_bound_rounded_to_float32", "double bound = (double)c->clamp;      /* exact comparison, as in orc_encode */",
+     "double bound = (double)(float)c->clamp;"),
     ("update_step_sign", "w[j] = avg - step;", "w[j] = avg + step;"),
     ("update_divides_by_k_plus_one", "volatile float inv_k = 1.0f / (float)K;", "volatile float inv_k = 1.0f / (float)(K + 1);"),
 ]

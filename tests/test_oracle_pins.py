@@ -239,6 +239,37 @@ def test_transform_roundtrip_and_linearity_large(orc):
         assert int(fd[j]) == pow(psi, 2 * j + 1, q)
 
 
+def test_batched_transforms_and_benchmark_polynomials(orc):
+    """The drivers of the transform micro-benchmark: polynomial (b, i) of a batch [B][L][N] is transformed
+    with limb i's modulus and root (against the O(N^2) definition and Python's pow), the inverse batch
+    undoes it, and the benchmark polynomials are Philox domain 8 with the batch index in the ciphertext
+    word and the limb in the tag (against the independent Python generator)."""
+    log2n, L, Bn = 5, 2, 3
+    n = 1 << log2n
+    qs = orc.find_primes(60, log2n, 1) + orc.find_primes(36, log2n, 1)       # two very different limbs
+    o = orc.Oracle(log2n, qs, 0, 21, 0, 1, SEED)
+    polys = o.bench_polys(Bn)
+    assert polys.shape == (Bn, L, n)
+    for b in range(Bn):
+        for i in range(L):
+            assert [int(v) for v in polys[b, i]] == pyref.uniform(SEED, 8, i, 0, 0, b, qs[i], n), (b, i)
+    assert len({tuple(polys[b, i]) for b in range(Bn) for i in range(L)}) == Bn * L
+    fwd = o.ntt_forward_batch(polys)
+    assert fwd.shape == polys.shape and not np.array_equal(fwd, polys)
+    for b in range(Bn):
+        for i in range(L):
+            psi = orc.find_psi(qs[i], log2n)
+            assert np.array_equal(fwd[b, i], orc.ntt_definition(polys[b, i], qs[i], psi)), (b, i)
+            for j in (0, 1, n - 1):
+                assert int(fwd[b, i, j]) == sum(int(polys[b, i, k]) * pow(psi, (2 * j + 1) * k, qs[i])
+                                                for k in range(n)) % qs[i]
+    assert np.array_equal(o.ntt_inverse_batch(fwd), polys)
+    # an inverse from data the forward batch has not made: delta_0 -> all ones, so ones -> delta_0
+    ones = np.ones((Bn, L, n), dtype=np.uint64)
+    back = o.ntt_inverse_batch(ones)
+    assert np.all(back[:, :, 0] == 1) and not back[:, :, 1:].any()
+
+
 # ---------------------------------------------------------------- scheme vs brute force
 def _toy(orc, log2n, bits, L, t, K, f, seed=SEED):
     qs = orc.find_primes(bits, log2n, L)
@@ -622,6 +653,31 @@ def test_coefficient_packing_cross_check(orc):
     clamp = o.encode_clamp()
     fixed = sum(np.clip(np.where(np.isnan(g), 0, np.rint(g * np.float32(4.0))), -clamp, clamp).astype(np.int64) for g in grads)
     assert np.array_equal(sums[1], (fixed.astype(np.float32) * np.float32(0.25)))
+
+
+def test_clamp_is_exact_for_a_31_bit_plaintext_modulus(orc):
+    """The clamp bound floor(((t-1)/2)/K_max) exceeds 2^24 for t above about 2^25 and then need not be a
+    float32: the rounded value is compared with it exactly, so K_max clamped terms still cannot wrap mod t."""
+    log2n, n, K = 3, 8, 3
+    t = orc.find_primes(31, log2n, 1)[0]
+    assert (1 << 30) < t < (1 << 31) and t % (2 * n) == 1
+    o = orc.Oracle(log2n, orc.find_primes(36, log2n, 2), t, 21, 0, K, SEED)
+    clamp = o.encode_clamp()
+    assert clamp == ((t - 1) // 2) // K and 3 * clamp <= (t - 1) // 2
+    up = np.float32(clamp)
+    if int(up) <= clamp:
+        up = np.nextafter(up, np.float32(np.inf))
+    assert int(up) > clamp                                  # the next float32 above the bound
+    assert int(np.float32(clamp)) != clamp, "pick a modulus whose bound is not a float32"
+    v = np.array([up, -up, np.inf, -np.inf, np.nextafter(up, np.float32(0)), 3.0e9, -3.0e9, 12345.0], dtype=np.float32)
+    want = [min(max(int(np.rint(x)) if np.isfinite(x) else (1 << 62) * (1 if x > 0 else -1), -clamp), clamp) for x in v]
+    assert want[0] == clamp and want[1] == -clamp and want[4] < clamp
+    pc = o.encode_coefficients(v)
+    assert [int(x) for x in pc[0]] == [w % t for w in want]
+    assert np.array_equal(orc.ntt_forward(o.encode(v)[0], t, o.psi_t), pc[0])
+    # three clamped terms add up without wrapping
+    s3 = ((pc.astype(object) * 3) % t).astype(np.uint64)
+    assert np.array_equal(o.decode_coefficients(s3, n), np.array([3 * w for w in want], dtype=np.float32))
 
 
 def test_decode_centres_at_the_boundary(orc):
