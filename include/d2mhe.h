@@ -15,6 +15,14 @@
  * Q = prod q_i, t plaintext modulus, Lambda = floor(Q/t), K members of a closed
  * neighbourhood {i} u N_i ("group"), C ciphertexts per gradient vector.
  *
+ * DEVIATION FROM A COEFFICIENT-FORM BOUNDARY.  Ciphertexts, decryption shares, key shares and public
+ * keys cross this boundary in EVALUATION FORM (the image of the negacyclic transform below), not as
+ * coefficient vectors of R_q: the formulas of Sec. 3.2 / Sec. 4.2 are ring identities, the transform
+ * is a ring isomorphism R_q -> Z_q^N, so the objects are the same protocol messages, and Encrypt
+ * then costs three forward transforms per limb and no inverse, a share one, Decrypt one inverse.
+ * Plaintexts and floats are in coefficient / natural form.  d2mhe_ntt_inverse turns any of these
+ * objects into the coefficient form of the paper, d2mhe_ntt_index_map publishes the storage order.
+ *
  * Data forms
  *   coefficient form : uint64 [..][N], natural order, canonical residues.
  *   evaluation form  : uint64 [..][N]; position p holds xhat[perm[p]], where
@@ -95,8 +103,15 @@ d2mhe_status d2mhe_ntt_index_map(const d2mhe_ctx *ctx, uint32_t *perm_host);
 /* host: psi_i of limb i (i == L: the slot root psi_t), for inspection.                   */
 uint64_t d2mhe_root(const d2mhe_ctx *ctx, uint32_t limb);
 
-/* ---- negacyclic transforms (R_q ring products, Sec. 3.2) -------------------------------- */
-/* polys [B][L][N] in place: coefficient form -> evaluation form and back.                */
+/* ---- negacyclic transforms ------------------------------------------------------------------ */
+/* Sec. 3.2 defines the ciphertext ring R_q = Z_q[X]/(X^N + 1) (N a power of two) and every scheme
+ * function as sums and products in it.  A product in R_q is the coefficient-wise product of the
+ * evaluations at the N odd powers of a primitive 2N-th root psi_i, per RNS limb q_i:
+ * forward  xhat[j] = sum_n x[n] psi_i^((2j+1) n) mod q_i,  inverse its inverse (including N^-1).
+ * polys [B][L][N] device memory, in place: polynomial (b, i) is transformed modulo q_i;
+ * coefficient form (natural order) <-> evaluation form (order of d2mhe_ntt_index_map), canonical
+ * residues in and out.  Ring degrees above 2^14 run as two kernels per direction.  B = 0: no-op.
+ * Errors: NULL ctx/polys, misaligned polys, B * L >= 2^31 (D2MHE_ERR_RANGE).                 */
 d2mhe_status d2mhe_ntt_forward(d2mhe_ctx *ctx, uint64_t *polys, uint32_t B, void *stream);
 d2mhe_status d2mhe_ntt_inverse(d2mhe_ctx *ctx, uint64_t *polys, uint32_t B, void *stream);
 /* Uniform benchmark polynomials (Philox domain 8), coefficient form, out [B][L][N].      */
@@ -113,9 +128,15 @@ d2mhe_status d2mhe_aggregate_pk(d2mhe_ctx *ctx, const uint64_t *const *pk0_share
                                 uint64_t *pk, void *stream);
 
 /* ---- per round (Alg. 2 lines 6-9) ---------------------------------------------------------- */
-/* Fixed point + slot packing: value c*N+j goes to slot j of plaintext c; r = rint(v 2^f)
- * (float32, ties to even), NaN -> 0, clamped; pt [C][N]; needs n_values <= C*N, the tail
- * is zero.                                                                                */
+/* Encoding of a float vector into plaintext polynomials.  Sec. 6 (implementation paragraph)
+ * packs many values into one plaintext's SIMD slots and converts floats to fixed point with an
+ * error below 2^-d; it gives no map, so this is the library's reading: r = rint(v 2^f) in float32
+ * (ties to even), NaN -> 0, clamped (exactly, as an integer) to +-floor(((t-1)/2)/K_max) so that a
+ * sum of K_max terms cannot wrap modulo t (+-inf saturate), z = r mod t in [0, t); value c*N + j is
+ * slot j of plaintext c, i.e. the plaintext polynomial m_c in R_t (Sec. 3.2) has
+ * m_c(psi_t^(2j+1)) = z[c*N + j] (inverse negacyclic transform modulo t, psi_t by the same rule as
+ * psi_i); all N slots are used.  grad: n_values floats (device); pt [C][N] coefficient form in
+ * [0, t); needs n_values <= C*N (else D2MHE_ERR_RANGE), slots past n_values are zero.          */
 d2mhe_status d2mhe_encode(d2mhe_ctx *ctx, const float *grad, uint64_t n_values, uint64_t *pt,
                           uint32_t C, void *stream);
 /* BFV.Encrypt (Sec. 3.2 item 3) under the collective key: ct_c = (Lambda m_c + mu p0 + e0,
@@ -123,7 +144,10 @@ d2mhe_status d2mhe_encode(d2mhe_ctx *ctx, const float *grad, uint64_t n_values, 
 d2mhe_status d2mhe_encrypt(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_t *pt, uint32_t C,
                            uint32_t party, uint32_t group, uint32_t ct_base, uint64_t *ct,
                            void *stream);
-/* BFV.Add: ct_acc += ct_in (C ciphertexts).                                              */
+/* BFV.Add (Sec. 3.2 item 4; Alg. 2 line 8 sums the neighbours' ciphertexts with it):
+ * ct_acc <- (ct_acc.c0 + ct_in.c0, ct_acc.c1 + ct_in.c1) mod q_i, coefficient-wise, for C
+ * ciphertexts [C][2][L][N] (the sum is the same in either data form; both operands must be in
+ * the same one).  ct_acc may equal ct_in.  Errors: NULL, misaligned.                            */
 d2mhe_status d2mhe_add(d2mhe_ctx *ctx, uint64_t *ct_acc, const uint64_t *ct_in, uint32_t C,
                        void *stream);
 /* Share of the collective decryption, Eq. (1) without the target-key terms:
@@ -136,7 +160,10 @@ d2mhe_status d2mhe_partial_decrypt(d2mhe_ctx *ctx, const uint64_t *sk_share, con
  * farther than L*2^-62 from a half-integer (always, unless decryption noise overflowed).   */
 d2mhe_status d2mhe_combine(d2mhe_ctx *ctx, const uint64_t *ct, const uint64_t *const *shares,
                            uint32_t K, uint32_t C, uint64_t *pt, void *stream);
-/* Inverse of d2mhe_encode: slots -> centred representatives -> float32 * 2^-f.           */
+/* Inverse of d2mhe_encode (same passage of Sec. 6): slots z[j] = m_c(psi_t^(2j+1)) by the forward
+ * transform modulo t, centred representative (z > (t-1)/2 -> z - t), out = float32(z) * 2^-f (both
+ * steps exact, hence a decoded sum equals the fixed-point sum bit for bit).  pt [C][N] in [0, t);
+ * out: n_values floats (device), n_values <= C*N.                                              */
 d2mhe_status d2mhe_decode(d2mhe_ctx *ctx, const uint64_t *pt, uint32_t C, uint64_t n_values,
                           float *out, void *stream);
 
@@ -157,8 +184,10 @@ d2mhe_status d2mhe_decode_coefficients(d2mhe_ctx *ctx, const uint64_t *pt, uint3
 typedef struct {
     uint32_t num_groups;             /* G >= 1                                              */
     const uint32_t *group_offsets;   /* [G+1], group_offsets[0] = 0, strictly increasing    */
-    const uint32_t *members;         /* [group_offsets[G]] party ids                        */
-    const uint32_t *group_ids;       /* [G] ids used in the Philox counter, NULL = 0..G-1   */
+    const uint32_t *members;         /* [group_offsets[G]] party ids <= 65535, no party twice
+                                        within one group                                     */
+    const uint32_t *group_ids;       /* [G] ids used in the Philox counter, pairwise distinct,
+                                        each <= 65535; NULL = 0..G-1                         */
     const uint64_t *const *pks;      /* [G] prepared public key of each group               */
     uint32_t num_parties;            /* P: size of the two tables below                     */
     const uint64_t *const *sk_shares;/* [P] prepared secret share by party id               */

@@ -1,5 +1,6 @@
 // C-ABI entry points of the d2mhe library (see include/d2mhe.h): parameter validation,
 // host-side table construction and kernel launches.  No device memory is allocated here.
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
@@ -697,6 +698,15 @@ d2mhe_status d2mhe_average_update(const float *sum, uint32_t K, const float *gra
 
 namespace {
 
+// a party listed twice among the (at most MAX_GROUP) members of a group
+bool has_duplicates(const uint32_t *members, uint32_t K)
+{
+    for (uint32_t a = 1; a < K; ++a)
+        for (uint32_t b = 0; b < a; ++b)
+            if (members[a] == members[b]) return true;
+    return false;
+}
+
 // words of scratch for J (party, group) jobs, G groups, C ciphertext indices; S conversion shares
 // (0: collective decryption, one single-polynomial share per job)
 size_t round_words(const d2mhe_ctx *ctx, uint64_t J, uint64_t G, uint64_t S, uint64_t C)
@@ -731,6 +741,18 @@ d2mhe_status run_round(d2mhe_ctx *ctx, const d2mhe_round_desc *d, const d2mhe_co
             if (misaligned(d->out_sums[g])) return D2MHE_ERR_ALIGN;
         }
     }
+    // The Philox counters hold 16 bits of group id and of party id, and a (party, group id) pair names one
+    // stream of randomness: ids beyond 16 bits, two groups with one id or a member listed twice in a group
+    // would make two encryptions share their mu, e0, e1.
+    if (d->group_ids) {
+        std::vector<uint32_t> ids(d->group_ids, d->group_ids + G);
+        std::sort(ids.begin(), ids.end());
+        if (ids.back() > 0xffffu) return D2MHE_ERR_RANGE;
+        if (std::adjacent_find(ids.begin(), ids.end()) != ids.end()) return D2MHE_ERR_RANGE;
+    }
+    for (uint32_t g = 0; g < G; ++g)
+        if (has_duplicates(d->members + d->group_offsets[g], d->group_offsets[g + 1] - d->group_offsets[g]))
+            return D2MHE_ERR_RANGE;
     for (uint32_t j = 0; j < J; ++j) {
         const uint32_t party = d->members[j];
         if (party >= d->num_parties || party > 0xffffu) return D2MHE_ERR_RANGE;
@@ -954,6 +976,7 @@ d2mhe_status d2mhe_round_group(d2mhe_ctx *ctx, const uint64_t *pk, const uint64_
     uint32_t offsets[2] = {0, K};
     for (uint32_t k = 0; k < K; ++k)
         if (members[k] > 0xffffu) return D2MHE_ERR_RANGE;
+    if (has_duplicates(members, K)) return D2MHE_ERR_RANGE;
     // pointer tables indexed by party id: build sparse views of size max id + 1
     uint32_t max_id = 0;
     for (uint32_t k = 0; k < K; ++k) max_id = members[k] > max_id ? members[k] : max_id;
@@ -996,6 +1019,7 @@ d2mhe_status d2mhe_round_group_static(d2mhe_ctx *ctx, const uint64_t *pk, const 
         if (!sk_shares[k] || !grads[k]) return D2MHE_ERR_NULL;
         if (misaligned(sk_shares[k]) || misaligned(grads[k])) return D2MHE_ERR_ALIGN;
     }
+    if (has_duplicates(members, K)) return D2MHE_ERR_RANGE;
     if (n_values == 0) return D2MHE_OK;
     const uint64_t C64 = (n_values + ctx->N - 1) / ctx->N;
     if (C64 > 0x7fffffffull) return D2MHE_ERR_RANGE;

@@ -398,10 +398,13 @@ D2_DEV void encode_to_regs(uint32_t (&m)[ENG::E], uint64_t *lds, int tid, const 
     auto fixed = [&](uint64_t gi) -> uint64_t {          // value gi as a residue mod t
         float v = gi < n_values ? grad[gi] : 0.0f;
         float r = (v != v) ? 0.0f : __builtin_rintf(v * rc.scale);
-        float bound = (float)rc.clamp;
-        r = r > bound ? bound : r;
-        r = r < -bound ? -bound : r;
+        // The clamp bound (< 2^30) need not be a float once it exceeds 2^24: bring the rounded value into
+        // the int32 range first (2^30 is a float), then compare as integers.
+        r = r > 0x1p30f ? 0x1p30f : r;
+        r = r < -0x1p30f ? -0x1p30f : r;
         int32_t z = (int32_t)r;
+        z = z > rc.clamp ? rc.clamp : z;
+        z = z < -rc.clamp ? -rc.clamp : z;
         return z >= 0 ? (uint64_t)z : t - (uint64_t)(uint32_t)(-z);
     };
     if (rc.coeff_packing) {                              // coefficient packing: no transform

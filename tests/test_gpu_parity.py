@@ -21,7 +21,7 @@ def fixed_point_sum(grads, f, clamp):
     for g in grads:
         r = np.rint(g.astype(np.float32) * np.float32(2.0 ** f))
         r = np.where(np.isnan(r), 0, r)
-        acc += np.clip(r, -clamp, clamp).astype(np.int64)
+        acc += np.clip(r.astype(np.float64), -clamp, clamp).astype(np.int64)     # exact bound, also above 2^24
     return (acc.astype(np.float32) * np.float32(2.0 ** -f)).astype(np.float32)
 
 
@@ -247,6 +247,29 @@ def test_edge_cases_ragged_tail_clamp_and_extreme_ids():
     ctx.close()
 
 
+def test_clamp_with_a_31_bit_plaintext_modulus():
+    """t just below 2^31: the clamp bound is above 2^24 and not a float32; values around it, both packings."""
+    log2n = 10
+    t = O.find_primes(31, log2n, 1)[0]
+    cfg = toy_config(log2n, O.find_primes(44, log2n, 2), t, parties=3, n_values=1024 + 9, frac_bits=0)
+    o, ctx, perm = make_pair(cfg, max_group=3)
+    clamp = o.encode_clamp()
+    assert clamp > (1 << 24) and int(np.float32(clamp)) != clamp
+    up = np.nextafter(np.float32(clamp), np.float32(np.inf)) if int(np.float32(clamp)) <= clamp else np.float32(clamp)
+    rng = np.random.default_rng(31)
+    grads = {k: (rng.normal(0, 1.0, cfg.n_values) * clamp).astype(np.float32) for k in range(3)}
+    for k in range(3):
+        grads[k][:6] = [up, -up, np.inf, -np.inf, np.nextafter(up, np.float32(0)), -3.0e9]
+    keys = Keys(o, ctx, perm, range(3))
+    run_calls_and_compare(cfg, o, ctx, perm, keys, [0, 1, 2], 1, grads)
+    C_ = cfg.C
+    for k in range(3):
+        dpt = dzeros(C_ * cfg.N)
+        ctx.encode_coefficients(to_dev(grads[k]), cfg.n_values, dpt, C_)
+        assert np.array_equal(to_host(dpt, (C_, cfg.N)), o.encode_coefficients(grads[k]))
+    ctx.close()
+
+
 def test_eta_and_small_prime_variants():
     """eta = 1 and eta = 32 (full words), a 30-bit prime next to 61-bit-class primes."""
     for (eta, bits, L, log2n) in [(1, 30, 1, 10), (32, 60, 2, 10), (7, 36, 4, 12)]:
@@ -339,6 +362,16 @@ def test_whole_round_argument_checks():
         with pytest.raises(B.D2mheError) as ei:
             ctx.round(ctx.make_round(groups_, pks_, sks, dgr, outs_, cfg.n_values), scratch, nbytes)
         assert ei.value.status == status
+    # ids that would alias Philox streams: a group id beyond 16 bits, two groups with one id, a member twice
+    for groups_, gids in (([[0, 1, 2, 3]], [70000]), ([[0, 1], [2, 3]], [5, 5]), ([[0, 1, 1]], None)):
+        with pytest.raises(B.D2mheError) as ei:
+            ctx.round(ctx.make_round(groups_, [pks[0][1]] * len(groups_), sks, dgr, outs * len(groups_), cfg.n_values,
+                                     group_ids=gids), scratch, nbytes)
+        assert ei.value.status == B.ERR_RANGE
+    with pytest.raises(B.D2mheError) as ei:
+        ctx.round_group(pks[0][1], [sks[0], sks[1], sks[0]], [dgr[0], dgr[1], dgr[0]], [0, 1, 0], 0, cfg.n_values, outs[0],
+                        scratch, nbytes)
+    assert ei.value.status == B.ERR_RANGE
     # a round over zero values is accepted and writes nothing
     before = outs[0].clone()
     ctx.round(ctx.make_round([[0, 1, 2, 3]], [pks[0][1]], sks, dgr, outs, 0), scratch, nbytes)
