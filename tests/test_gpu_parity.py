@@ -247,6 +247,45 @@ def test_edge_cases_ragged_tail_clamp_and_extreme_ids():
     ctx.close()
 
 
+@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+def test_coefficient_form_export_equals_the_oracles_objects(name):
+    """The library's messages are in evaluation form; d2mhe_ntt_inverse turns them into the coefficient form
+    the paper's formulas are written in.  A public key, fresh ciphertexts, their sum and a decryption share go
+    through it and are compared with the oracle's coefficient-form objects directly (no oracle transform)."""
+    cfg = CONFIGS[name]
+    o, ctx, perm = make_pair(cfg)
+    L, N = cfg.L, cfg.N
+    n_values = 2 * N + 5
+    members = cfg.groups()[1 if name != "C1" else 0]
+    grads = {k: g[:n_values] for k, g in enumerate(cfg.gradients(n_values=n_values)) if k in members}
+    keys = Keys(o, ctx, perm, members, check=False)
+    opk, dpk = keys.group_pk(members, perm, check=False)
+    C_ = 3
+    coeff = lambda t, B: (ctx.ntt_inverse(t, B), to_host(t))[1]
+    pkv = dpk.view(2, 2, L * N)[:, 0].contiguous()                 # values of (p0, p1) without the quotients
+    assert np.array_equal(coeff(pkv, 2).reshape(2, L, N), opk), "collective public key"
+    dagg, oagg = None, None
+    for k in members:
+        dpt = dzeros(C_ * N)
+        ctx.encode(to_dev(grads[k]), n_values, dpt, C_)
+        dct = dzeros(C_ * 2 * L * N)
+        ctx.encrypt(dpk, dpt, C_, k, 1, 7, dct)
+        oct_ = o.encrypt(opk, o.encode(grads[k]), k, 1, 7)
+        if dagg is None:
+            dagg, oagg = dct.clone(), oct_
+        else:
+            ctx.add(dagg, dct, C_)
+            oagg = o.add(oagg, oct_)
+        assert np.array_equal(coeff(dct, 2 * C_).reshape(oct_.shape), oct_), f"fresh ciphertexts of party {k}"
+    k = members[-1]
+    dsh = dzeros(C_ * L * N)
+    ctx.partial_decrypt(keys.sk[k], dagg, C_, k, 1, 7, dsh)
+    osh = o.partial_decrypt(keys.osk[k], oagg, k, 1, 7)
+    assert np.array_equal(coeff(dsh, C_).reshape(osh.shape), osh), "decryption share"
+    assert np.array_equal(coeff(dagg, 2 * C_).reshape(oagg.shape), oagg), "aggregate"
+    ctx.close()
+
+
 def test_clamp_with_a_31_bit_plaintext_modulus():
     """t just below 2^31: the clamp bound is above 2^24 and not a float32; values around it, both packings."""
     log2n = 10
