@@ -34,13 +34,15 @@ JOBS_PER_LAUNCH = 112                      # (party, group) pairs one launch of 
 
 def ops_per_butterfly(qmax):
     """VALU instructions of one butterfly in the minimal sequence of each arithmetic back-end
-    (csrc/arith.hpp): doubles for moduli < 2^44, 63-bit Shoup with an approximate quotient for
-    moduli < 2^55, exact Harvey butterflies for moduli < 2^61."""
+    (csrc/arith.hpp): 32-bit Harvey butterflies for moduli < 2^30, doubles for moduli < 2^44, 63-bit
+    Shoup with an approximate quotient for moduli < 2^55, exact Harvey butterflies for moduli < 2^61."""
+    if qmax < (1 << 30):
+        return 8, "u32-harvey"
     if qmax < (1 << 44):
         return 8, "f64"
     if qmax < (1 << 55):
-        return 16, "u64-lazy"
-    return 22, "u64-harvey"
+        return 15, "u64-lazy"
+    return 21, "u64-harvey"
 
 
 def profiled_traffic(workload, kernel):
@@ -276,8 +278,8 @@ def main():
         "value": fig["fresh_ct_per_s"], "unit": "fresh ciphertexts/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u64" if w.arith != "f64" else "f64",
-        "dtype_note": "residues below 2^44 are held as exact integers in doubles, wider ones as 64-bit integers",
+        "dtype": {"f64": "f64", "u32-harvey": "u32"}.get(w.arith, "u64"),
+        "dtype_note": "residues below 2^30 are 32-bit integers, below 2^44 exact integers in doubles, wider ones 64-bit integers",
         "data": "synthetic",
         "config": {"workload": fig["workload"], "fresh_ciphertexts": fig["fresh_ciphertexts"],
                    "aggregated_ciphertexts": fig["aggregated_ciphertexts"],

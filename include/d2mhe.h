@@ -79,7 +79,7 @@ typedef struct {
     uint32_t log2_n;      /* 10..16                                                         */
     uint32_t num_limbs;   /* L, 1..16                                                       */
     const uint64_t *q;    /* host: L distinct primes < 2^61, q_i = 1 (mod 2N)               */
-    uint64_t t;           /* prime, t = 1 (mod 2N), t < 2^31, t < min q_i;
+    uint64_t t;           /* prime, t = 1 (mod 2N), t < 2^30, t < min q_i;
                              0 = transform-only context (no encode/encrypt/decrypt)         */
     uint32_t cbd_eta;     /* 1..32: error = popcount(eta bits) - popcount(eta bits)          */
     uint32_t frac_bits;   /* f: fixed-point fraction bits, 0..30                            */

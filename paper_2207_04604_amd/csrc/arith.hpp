@@ -13,6 +13,10 @@
 //           never corrected inside a forward transform (65 q < 2^62).
 //   ArithB  (moduli < 2^61)  64-bit integers, exact 63-bit Shoup quotient, Harvey's lazy
 //           butterflies: forward values in [0, 4q), inverse values in [0, 2q).
+//   Arith32 (moduli < 2^30)  32-bit residues (one register and one 4-byte LDS word per
+//           coefficient), 32-bit Shoup quotient ws = floor(w 2^32 / q), Harvey's lazy butterflies
+//           in 8 instructions.  Used for whole contexts whose primes are below 2^30 and, in every
+//           context, for the transforms modulo the plaintext modulus t.
 //
 // Table entries (twiddles, per-modulus constants) are {w, floor(w 2^63 / q)} for the integer
 // policies and {bits of the double w, unused} for ArithF.  Prepared keys cross the library
@@ -163,7 +167,9 @@ struct TwU {        // multiplicand and its 63-bit Shoup quotient
 // w*y - qh*q mod 2^64, written as w*y + qh*(2^64 - q) so that every term is added:
 // a chain of four 64-bit multiply-adds for the cross terms (only its low word matters; it is
 // shifted up by 32), then two more for the low x low terms on top of it.
-// SC: w sits in scalar registers (a multiplicand shared by the whole wavefront).
+// SC: w sits in scalar registers (a multiplicand shared by the whole wavefront).  2^64 - q is the same
+// for the whole workgroup and always comes from scalar registers (no instruction here reads both it
+// and w, so the one-scalar-operand limit holds).
 #define D2_SHOUP_TAIL_ASM(WC)                                                                      \
     asm("v_mad_u64_u32 %1, vcc, %4, %3, 0\n\t"                                                     \
         "v_mad_u64_u32 %1, vcc, %5, %2, %1\n\t"                                                    \
@@ -173,7 +179,7 @@ struct TwU {        // multiplicand and its 63-bit Shoup quotient
         "v_mad_u64_u32 %0, vcc, %4, %2, %1\n\t"                                                    \
         "v_mad_u64_u32 %0, vcc, %6, %8, %0"                                                        \
         : "=&v"(acc), "=&v"(cross)                                                                 \
-        : "v"(y0), "v"(y1), WC(w0), WC(w1), "v"(h0), "v"(h1), "v"(n0), "v"(n1)                     \
+        : "v"(y0), "v"(y1), WC(w0), WC(w1), "v"(h0), "v"(h1), "s"(n0), "s"(n1)                     \
         : "vcc")
 template <bool SC = false>
 D2_DEV uint64_t shoup_tail(uint64_t y, uint64_t w, uint64_t qh, uint64_t nq)
@@ -187,6 +193,41 @@ D2_DEV uint64_t shoup_tail(uint64_t y, uint64_t w, uint64_t qh, uint64_t nq)
     return acc;
 #else
     uint64_t acc = mul32(w0, y0);
+    acc = mul32(h0, n0) + acc;
+    const uint32_t cross = w0 * y1 + w1 * y0 + h0 * n1 + h1 * n0;
+    return acc + ((uint64_t)cross << 32);
+#endif
+}
+
+// u + (w*y - qh*q) mod 2^64: the addend rides on the multiply-add chain of the low x low terms, and the
+// cross terms, of which only the low word matters, are added to the high word at the end: one
+// instruction less than shoup_tail followed by a 64-bit addition, and two independent chains.
+#define D2_SHOUP_TAIL_ADD_ASM(WC)                                                                  \
+    asm("v_mad_u64_u32 %1, vcc, %4, %3, 0\n\t"                                                     \
+        "v_mad_u64_u32 %0, vcc, %4, %2, %10\n\t"                                                   \
+        "v_mad_u64_u32 %1, vcc, %5, %2, %1\n\t"                                                    \
+        "v_mad_u64_u32 %0, vcc, %6, %8, %0\n\t"                                                    \
+        "v_mad_u64_u32 %1, vcc, %6, %9, %1\n\t"                                                    \
+        "v_mad_u64_u32 %1, vcc, %7, %8, %1"                                                        \
+        : "=&v"(acc), "=&v"(cross)                                                                 \
+        : "v"(y0), "v"(y1), WC(w0), WC(w1), "v"(h0), "v"(h1), "s"(n0), "s"(n1), "v"(u)             \
+        : "vcc")
+template <bool SC = false>
+D2_DEV uint64_t shoup_tail_add(uint64_t y, uint64_t w, uint64_t qh, uint64_t nq, uint64_t u)
+{
+    const uint32_t y0 = lo32(y), y1 = hi32(y), w0 = lo32(w), w1 = hi32(w);
+    const uint32_t h0 = lo32(qh), h1 = hi32(qh), n0 = lo32(nq), n1 = hi32(nq);
+#if D2_GCN_ASM
+    uint64_t acc, cross;
+    if constexpr (SC) D2_SHOUP_TAIL_ADD_ASM("s");
+    else D2_SHOUP_TAIL_ADD_ASM("v");
+    // one 32-bit addition on the high word (written out: as C it comes back as a move plus a 64-bit add)
+    uint32_t top = hi32(acc);
+    const uint32_t cl = lo32(cross);
+    asm("v_add_u32 %0, %0, %1" : "+v"(top) : "v"(cl));
+    return ((uint64_t)top << 32) | lo32(acc);
+#else
+    uint64_t acc = mul32(w0, y0) + u;
     acc = mul32(h0, n0) + acc;
     const uint32_t cross = w0 * y1 + w1 * y0 + h0 * n1 + h1 * n0;
     return acc + ((uint64_t)cross << 32);
@@ -264,6 +305,7 @@ D2_DEV uint64_t qhat_exact(uint64_t y, uint64_t ws)
 // ---------------------------------------------------------------------------------------
 struct ArithS {
     typedef uint64_t elem;
+    typedef uint64_t word;          // LDS word of an exchange
     typedef ModU Mod;
     typedef TwU Twid;
     static constexpr int KIND = 1;
@@ -302,16 +344,17 @@ struct ArithS {
     D2_DEV static elem from_canon(uint64_t v, const Mod &) { return v; }
     D2_DEV static elem add(elem a, elem b) { return a + b; }
 
-    // forward: no correction; each stage adds at most 4q to the bound
+    // forward: no correction; each stage adds at most 4q to the bound.
+    // x' = u + t comes out of the multiply-add chain itself, y' = u + 4q - t = (2u + 4q) - x'.
     template <bool SC = false>
     D2_DEV static void ct(elem &x, elem &y, const Twid &w, const Mod &m)
     {
-        const elem t = mul<SC>(y, w, m);
         const elem u = x;
-        x = u + t;
-        y = u + 4 * m.q - t;
+        x = shoup_tail_add<SC>(y, w.w, qhat_approx<SC>(y, w.ws), m.nq, u);
+        y = (2 * u + 4 * m.q) - x;
     }
     D2_DEV static void fwd_pass_begin(elem &, const Mod &) {}
+    D2_DEV static void fwd_end(elem &, const Mod &) {}
     // inverse: values in [0, 4q)
     template <bool SC = false>
     D2_DEV static void gs(elem &x, elem &y, const Twid &w, const Mod &m)
@@ -350,6 +393,7 @@ struct ArithS {
 // ---------------------------------------------------------------------------------------
 struct ArithB {
     typedef uint64_t elem;
+    typedef uint64_t word;          // LDS word of an exchange
     typedef ModU Mod;
     typedef TwU Twid;
     static constexpr int KIND = 2;
@@ -394,11 +438,11 @@ struct ArithB {
     {
         const elem two_q = 2 * m.q;
         const elem u = csub(x, two_q);
-        const elem t = mul<SC>(y, w, m);
-        x = u + t;
-        y = u + two_q - t;
+        x = shoup_tail_add<SC>(y, w.w, qhat_exact<SC>(y, w.ws), m.nq, u);       // u + t
+        y = (2 * u + two_q) - x;                                                // u + 2q - t
     }
     D2_DEV static void fwd_pass_begin(elem &, const Mod &) {}
+    D2_DEV static void fwd_end(elem &, const Mod &) {}
     // x, y in [0, 2q) -> [0, 2q)
     template <bool SC = false>
     D2_DEV static void gs(elem &x, elem &y, const Twid &w, const Mod &m)
@@ -436,6 +480,7 @@ struct ArithB {
 // ---------------------------------------------------------------------------------------
 struct ArithF {
     typedef double elem;
+    typedef uint64_t word;          // LDS word of an exchange
     struct Mod {
         double q, qinv;
         uint64_t qi;
@@ -507,6 +552,7 @@ struct ArithF {
         y = u - t;
     }
     D2_DEV static void fwd_pass_begin(elem &, const Mod &) {}
+    D2_DEV static void fwd_end(elem &, const Mod &) {}
     template <bool SC = false>
     D2_DEV static void gs(elem &x, elem &y, const Twid &w, const Mod &m)
     {
@@ -539,6 +585,106 @@ struct ArithF {
     D2_DEV static uint64_t canon_acc(elem x, const Mod &m) { return canon_wide(x, m); }
 };
 
+// ---------------------------------------------------------------------------------------
+// Arith32: moduli < 2^30, 32-bit residues, Harvey butterflies with a 32-bit Shoup quotient.
+// Forward values in [0, 4q) (< 2^32), a finished forward transform in [0, 2q) so that one more lazy
+// product can be added without overflow; inverse values in [0, 2q).
+// Table entries hold {w | floor(w 2^32 / q) << 32, -} (8 bytes are read per twiddle).
+// ---------------------------------------------------------------------------------------
+struct Arith32 {
+    typedef uint32_t elem;
+    typedef uint32_t word;          // LDS word of an exchange
+    struct Mod {
+        uint32_t q, two_q, nq;      // nq = 2^32 - q
+        uint32_t one_s;             // floor(2^32 / q)
+    };
+    struct Twid {
+        uint32_t w, ws;
+    };
+    static constexpr int KIND = 3;
+
+    D2_DEV static Mod mod(uint64_t q, uint64_t one_s32) { return Mod{(uint32_t)q, 2u * (uint32_t)q, 0u - (uint32_t)q, (uint32_t)one_s32}; }
+    D2_DEV static Mod mod(uint64_t q) { return mod(q, (1ull << 32) / q); }
+    D2_DEV static Twid tw(const Tw &t) { return Twid{lo32(t.w), hi32(t.w)}; }
+    D2_DEV static Twid tw(uint64_t w, uint64_t ws64) { return Twid{(uint32_t)w, hi32(ws64)}; }
+    // element of a prepared key: values at v, 64-bit quotients at vs (their high words are the 32-bit quotients)
+    D2_DEV static Twid key(const uint64_t *v, const uint64_t *vs, uint32_t lane_off, uint32_t slot_off)
+    {
+        return tw(ld64(v, lane_off, slot_off), ld64(vs, lane_off, slot_off));
+    }
+    static constexpr bool SCALAR_TW = true;
+    D2_DEV static Twid load_v(const Tw *table, uint32_t i)
+    {
+        const uint64_t e = ld64(table, 16u * i, 0);
+        return Twid{lo32(e), hi32(e)};
+    }
+    D2_DEV static Twid load_u(const Tw *table, uint32_t i)
+    {
+        const uint64_t e = const_ld64(table, 16u * i);
+        return Twid{lo32(e), hi32(e)};
+    }
+
+    // x >= m ? x - m : x for x < 2m: the smaller of x and x - m as unsigned numbers
+    D2_DEV static uint32_t csub32(uint32_t x, uint32_t m)
+    {
+        const uint32_t d = x - m;
+        return d < x ? d : x;
+    }
+    // w*y mod q in [0, 2q), for any 32-bit y: the low word of w y + floor(ws y / 2^32) (2^32 - q)
+    template <bool SC = false>
+    D2_DEV static elem mul(elem y, const Twid &w, const Mod &m)
+    {
+        const uint32_t qh = __umulhi(y, w.ws);
+        return (uint32_t)(mul32(w.w, y) + mul32(qh, m.nq));
+    }
+    D2_DEV static elem from_small(int32_t v, const Mod &m) { return v >= 0 ? (uint32_t)v : m.q - (uint32_t)(-v); }
+    D2_DEV static elem from_canon(uint64_t v, const Mod &) { return (uint32_t)v; }
+    D2_DEV static elem add(elem a, elem b) { return a + b; }
+
+    // x, y in [0, 4q) -> [0, 4q)
+    template <bool SC = false>
+    D2_DEV static void ct(elem &x, elem &y, const Twid &w, const Mod &m)
+    {
+        const elem u = csub32(x, m.two_q);
+        const elem t = mul<SC>(y, w, m);
+        x = u + t;
+        y = u + m.two_q - t;
+    }
+    D2_DEV static void fwd_pass_begin(elem &, const Mod &) {}
+    // the last step of a forward transform: [0, 4q) -> [0, 2q)
+    D2_DEV static void fwd_end(elem &x, const Mod &m) { x = csub32(x, m.two_q); }
+    // x, y in [0, 2q) -> [0, 2q)
+    template <bool SC = false>
+    D2_DEV static void gs(elem &x, elem &y, const Twid &w, const Mod &m)
+    {
+        const elem s = x + y, d = x + m.two_q - y;
+        x = csub32(s, m.two_q);
+        y = mul<SC>(d, w, m);
+    }
+    template <bool SC = false>
+    D2_DEV static void gs_last(elem &x, elem &y, const Twid &ninv, const Twid &wn, const Mod &m)
+    {
+        const elem s = x + y, d = x + m.two_q - y;
+        x = mul<SC>(s, ninv, m);
+        y = mul<SC>(d, wn, m);
+    }
+    D2_DEV static void inv_pass_begin(elem &, const Mod &) {}
+    D2_DEV static elem inv_input(uint64_t canon, const Mod &) { return (uint32_t)canon; }
+
+    // [0, 4q) -> [0, q)
+    D2_DEV static uint64_t canon_lazy(elem x, const Mod &m) { return csub32(csub32(x, m.two_q), m.q); }
+    // any 32-bit value -> [0, q)
+    D2_DEV static uint64_t canon_wide(elem x, const Mod &m)
+    {
+        const uint32_t r = x - __umulhi(x, m.one_s) * m.q;        // [0, 2q)
+        return csub32(r, m.q);
+    }
+    D2_DEV static uint64_t canon_fwd(elem x, const Mod &m) { return canon_lazy(x, m); }
+    D2_DEV static uint64_t canon_inv(elem x, const Mod &m) { return csub32(x, m.q); }
+    // finished forward transform ([0, 2q)) + one lazy product ([0, 2q))
+    D2_DEV static uint64_t canon_acc(elem x, const Mod &m) { return canon_lazy(x, m); }
+};
+
 // canonical u64 helpers used outside the transforms
 D2_DEV uint64_t add_mod(uint64_t a, uint64_t b, uint64_t q) { return csub(a + b, q); }
 // w*y mod q, canonical, with the 64-bit Shoup quotient ws64 = floor(w 2^64 / q); any 64-bit y
@@ -548,7 +694,8 @@ D2_DEV uint64_t mul_shoup64(uint64_t y, uint64_t w, uint64_t ws64, uint64_t q)
     return csub(r, q);
 }
 
-// uint64 <-> element bit patterns for LDS and lazily stored intermediates
+// uint64 <-> element bit patterns for lazily stored intermediates and 8-byte LDS words; a policy with
+// 4-byte LDS words (Arith32) stores its elements as they are
 template <class A>
 D2_DEV uint64_t to_bits(typename A::elem v);
 template <>
@@ -558,13 +705,31 @@ D2_DEV uint64_t to_bits<ArithB>(uint64_t v) { return v; }
 template <>
 D2_DEV uint64_t to_bits<ArithF>(double v) { return (uint64_t)__double_as_longlong(v); }
 
+template <>
+D2_DEV uint64_t to_bits<Arith32>(uint32_t v) { return v; }
+
 template <class A>
 D2_DEV typename A::elem from_bits(uint64_t v);
+template <>
+D2_DEV uint32_t from_bits<Arith32>(uint64_t v) { return (uint32_t)v; }
 template <>
 D2_DEV uint64_t from_bits<ArithS>(uint64_t v) { return v; }
 template <>
 D2_DEV uint64_t from_bits<ArithB>(uint64_t v) { return v; }
 template <>
 D2_DEV double from_bits<ArithF>(uint64_t v) { return __longlong_as_double((long long)v); }
+
+template <class A>
+D2_DEV typename A::word to_word(typename A::elem v)
+{
+    if constexpr (sizeof(typename A::word) == 8) return to_bits<A>(v);
+    else return v;
+}
+template <class A>
+D2_DEV typename A::elem from_word(typename A::word v)
+{
+    if constexpr (sizeof(typename A::word) == 8) return from_bits<A>(v);
+    else return v;
+}
 
 }  // namespace d2

@@ -13,7 +13,7 @@ struct d2mhe_ctx {
     uint64_t psi[d2::MAX_LIMBS + 1];
     uint64_t t;
     uint32_t max_group;
-    int arith;          // 0: ArithF, 1: ArithS, 2: ArithB
+    int arith;          // 0: ArithF, 1: ArithS, 2: ArithB, 3: Arith32
     d2::RoundConst rc;
     const d2::LimbTab *d_tabs;
     uint64_t *d_p1;     // prepared common random polynomial [2][L][N]
@@ -92,5 +92,12 @@ const EngineOps *ops_b_13();
 const EngineOps *ops_b_14();
 const EngineOps *ops_b_15();
 const EngineOps *ops_b_16();
+const EngineOps *ops_w_10();
+const EngineOps *ops_w_11();
+const EngineOps *ops_w_12();
+const EngineOps *ops_w_13();
+const EngineOps *ops_w_14();
+const EngineOps *ops_w_15();
+const EngineOps *ops_w_16();
 
 }  // namespace d2

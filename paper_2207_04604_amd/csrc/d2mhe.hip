@@ -86,20 +86,24 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- engine shape per ring degree ----------------------------------------------------------
 typedef const EngineOps *(*OpsGetter)();
-const OpsGetter OPS_TABLE[3][7] = {
+const OpsGetter OPS_TABLE[4][7] = {
     {ops_f_10, ops_f_11, ops_f_12, ops_f_13, ops_f_14, ops_f_15, ops_f_16},
     {ops_s_10, ops_s_11, ops_s_12, ops_s_13, ops_s_14, ops_s_15, ops_s_16},
     {ops_b_10, ops_b_11, ops_b_12, ops_b_13, ops_b_14, ops_b_15, ops_b_16},
+    {ops_w_10, ops_w_11, ops_w_12, ops_w_13, ops_w_14, ops_w_15, ops_w_16},
 };
+constexpr int ARITH_32 = 3;
 
 const EngineOps *engine_ops(const d2mhe_ctx *ctx) { return OPS_TABLE[ctx->arith][ctx->log2n - 10](); }
 
-// Arithmetic back-end from the largest modulus: doubles below 2^44, 63-bit Shoup with an
-// approximate quotient below 2^55, exact Harvey butterflies otherwise.
+// Arithmetic back-end from the largest modulus: 32-bit residues below 2^30, doubles below 2^44,
+// 63-bit Shoup with an approximate quotient below 2^55, exact Harvey butterflies otherwise.
+// Transforms modulo the plaintext modulus (< 2^30) always use the 32-bit back-end.
 int arith_for(const d2mhe_params *p)
 {
     uint64_t qmax = 0;
     for (uint32_t i = 0; i < p->num_limbs; ++i) qmax = p->q[i] > qmax ? p->q[i] : qmax;
+    if (qmax < (1ull << 30)) return ARITH_32;
     if (qmax < (1ull << 44)) return 0;
     if (qmax < (1ull << 55)) return 1;
     return 2;
@@ -112,6 +116,9 @@ Tw h_entry(int arith, uint64_t w, uint64_t m)
     if (arith == 0) {
         const double d = (double)w;          // exact: w < 2^44
         std::memcpy(&t.w, &d, sizeof(d));
+        t.ws = 0;
+    } else if (arith == ARITH_32) {
+        t.w = w | ((w << 32) / m) << 32;     // value and floor(w 2^32 / m) in one 8-byte word
         t.ws = 0;
     } else {
         t.w = w;
@@ -150,7 +157,7 @@ bool params_ok(const d2mhe_params *p)
             if (p->q[j] == q) return false;
     }
     if (p->t) {
-        if (p->t >> 31) return false;
+        if (p->t >> 30) return false;
         if (p->t % two_n != 1 || !h_is_prime(p->t)) return false;
         for (uint32_t i = 0; i < p->num_limbs; ++i)
             if (p->t >= p->q[i]) return false;
@@ -251,7 +258,6 @@ d2mhe_status d2mhe_create(const d2mhe_params *p, void *dev_workspace, size_t byt
     ctx->t = p->t;
     ctx->max_group = p->max_group;
     ctx->arith = arith_for(p);
-    const int ar = ctx->arith;
     ctx->last_hip = 0;
     // Long transforms run as launch pairs over at most 65535 polynomials (grid.y limit).  Smaller
     // chunks (to keep a chunk in the memory-side cache between the two kernels) were measured
@@ -271,6 +277,7 @@ d2mhe_status d2mhe_create(const d2mhe_params *p, void *dev_workspace, size_t byt
     for (uint32_t i = 0; i < moduli; ++i) {
         // slot L of the table array is the plaintext modulus
         const uint64_t m = i < L ? p->q[i] : p->t;
+        const int ar = i < L ? ctx->arith : ARITH_32;      // table format of this modulus
         const uint64_t psi = h_root(m, log2n);
         if (i < L) ctx->q[i] = m;
         ctx->psi[i < L ? i : L] = psi;
@@ -286,6 +293,8 @@ d2mhe_status d2mhe_create(const d2mhe_params *p, void *dev_workspace, size_t byt
         if (ar == 0) {
             const double qinv = 1.0 / (double)m;
             std::memcpy(&tb.one_s, &qinv, sizeof(qinv));
+        } else if (ar == ARITH_32) {
+            tb.one_s = ((uint64_t)1 << 32) / m;
         } else {
             tb.one_s = (uint64_t)(((u128)1 << 63) / m);
         }

@@ -14,12 +14,13 @@ constexpr int MAX_LIMBS = 16;
 constexpr int MAX_GROUP = 64;
 
 // Per-modulus constants; entry L of the table array describes the plaintext modulus t.
-// Tw entries are in the context's arithmetic format ({w, floor(w 2^63/q)} for the integer
-// policies, {bits of the double w, -} for the floating-point policy), except `gamma`, which
-// is always {w, floor(w 2^64/q)} (the scale-and-round step runs on canonical integers).
+// Tw entries are in the context's arithmetic format ({w, floor(w 2^63/q)} for the 64-bit integer
+// policies, {bits of the double w, -} for the floating-point policy, {w | floor(w 2^32/q) << 32, -} for
+// the 32-bit policy; the entry of the plaintext modulus is always in the 32-bit format), except
+// `gamma` and `pow32`, which are always {w, floor(w 2^64/q)} (they work on canonical 64-bit integers).
 struct LimbTab {
     uint64_t q;
-    uint64_t one_s;     // floor(2^63 / q); floating-point policy: bits of the double 1/q
+    uint64_t one_s;     // floor(2^63 / q); floating-point policy: bits of the double 1/q; 32-bit policy: floor(2^32 / q)
     Tw ninv;            // N^-1 mod q
     Tw wn;              // (inverse twiddle 1) * N^-1 mod q
     Tw lambda;          // floor(Q/t) mod q
@@ -392,7 +393,10 @@ template <class ENG>
 D2_DEV void encode_to_regs(uint32_t (&m)[ENG::E], uint64_t *lds, int tid, const float *grad, uint64_t first,
                            uint64_t n_values, const LimbTab &tt, const RoundConst &rc)
 {
-    typedef typename ENG::A A;
+    // the plaintext modulus is below 2^30: its transform runs on 32-bit residues whatever the context's
+    // own arithmetic is (same thread shape and ownership)
+    typedef typename ENG::template Rebind<Arith32> TE;
+    typedef Arith32 A;
     const uint64_t t = tt.q;
     const typename A::Mod md = A::mod(t, tt.one_s);
     auto fixed = [&](uint64_t gi) -> uint64_t {          // value gi as a residue mod t
@@ -420,7 +424,7 @@ D2_DEV void encode_to_regs(uint32_t (&m)[ENG::E], uint64_t *lds, int tid, const 
 #pragma unroll
     for (int k = 0; k < ENG::E; ++k)
         x[k] = A::inv_input(lds[ENG::phys((int)bitrev((uint32_t)(tid * ENG::E + k), ENG::LOGB))], md);
-    ENG::template inverse<true>(x, lds, tid, 0, tt.inv, md, A::tw(tt.ninv), A::tw(tt.wn));
+    TE::template inverse<true>(x, lds, tid, 0, tt.inv, md, A::tw(tt.ninv), A::tw(tt.wn));
 #pragma unroll
     for (int k = 0; k < ENG::E; ++k) m[k] = (uint32_t)A::canon_inv(x[k], md);
 }
@@ -430,7 +434,8 @@ template <class ENG>
 D2_DEV void decode_from_regs(uint32_t (&m)[ENG::E], uint64_t *lds, int tid, float *out, uint64_t first,
                              uint64_t n_values, const LimbTab &tt, const RoundConst &rc)
 {
-    typedef typename ENG::A A;
+    typedef typename ENG::template Rebind<Arith32> TE;       // as in encode_to_regs
+    typedef Arith32 A;
     const uint64_t t = tt.q;
     const typename A::Mod md = A::mod(t, tt.one_s);
     if (rc.coeff_packing) {                              // coefficient packing: no transform
@@ -447,7 +452,7 @@ D2_DEV void decode_from_regs(uint32_t (&m)[ENG::E], uint64_t *lds, int tid, floa
     typename A::elem x[ENG::E];
 #pragma unroll
     for (int k = 0; k < ENG::E; ++k) x[k] = A::from_canon((uint64_t)m[k], md);
-    ENG::forward(x, lds, tid, 0, tt.fwd, md);
+    TE::forward(x, lds, tid, 0, tt.fwd, md);
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < ENG::E; ++k)
@@ -613,27 +618,35 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
             x[k] = A::add(A::mul(A::from_canon((uint64_t)opaque(m[k]), md), lam, md),
                           A::from_small(sbyte(opaque(smp[k]), 1), md));
         ENG::forward_chained(x, lds, turn, opaque(tl), 0, tb.fwd, md);
-        // the key values are requested in one batch (a load placed after a store of the previous
-        // slot could not be moved in front of it)
-        typename A::Twid kv[E];
+        // the key values are requested in batches of eight slots (a load placed after a store of the
+        // previous slot could not be moved in front of it; sixteen at once exceed the register budget)
+        constexpr int BATCH = E < 8 ? E : 8;
 #pragma unroll
-        for (int k = 0; k < E; ++k) kv[k] = A::key(p0, p0s, 8u * (uint32_t)tl, 8u * ENG::T * k);
+        for (int k0 = 0; k0 < E; k0 += BATCH) {
+            typename A::Twid kv[BATCH];
 #pragma unroll
-        for (int k = 0; k < E; ++k) {
-            const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
-            const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k];
-            st64(out + off, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k]), md));
+            for (int k = 0; k < BATCH; ++k) kv[k] = A::key(p0, p0s, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
+#pragma unroll
+            for (int k = 0; k < BATCH; ++k) {
+                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * (k0 + k);
+                const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k0 + k];
+                st64(out + off, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k0 + k]), md));
+            }
         }
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(opaque(smp[k]), 2), md);
         ENG::forward_chained(x, lds, turn, opaque(tl), 0, tb.fwd, md);
 #pragma unroll
-        for (int k = 0; k < E; ++k) kv[k] = A::key(p1, p1s, 8u * (uint32_t)tl, 8u * ENG::T * k);
+        for (int k0 = 0; k0 < E; k0 += BATCH) {
+            typename A::Twid kv[BATCH];
 #pragma unroll
-        for (int k = 0; k < E; ++k) {
-            const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
-            const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k];
-            st64(stash, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k]), md));
+            for (int k = 0; k < BATCH; ++k) kv[k] = A::key(p1, p1s, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
+#pragma unroll
+            for (int k = 0; k < BATCH; ++k) {
+                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * (k0 + k);
+                const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k0 + k];
+                st64(stash, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k0 + k]), md));
+            }
         }
     }
 }
@@ -669,18 +682,24 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_share(ShareJobs jobs, ui
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = A::from_small(opaque(e[k]), md);
         ENG::forward_chained(x, lds, turn, tl, 0, tb.fwd, md);
-        typename A::Twid kv[E];
-        uint64_t cv[E];
+        // key and ciphertext values are requested eight slots at a time: a batch of sixteen (six registers
+        // per slot next to the transform's output) does not fit the register budget
+        constexpr int BATCH = E < 8 ? E : 8;
 #pragma unroll
-        for (int k = 0; k < E; ++k) {
-            kv[k] = A::key(sk + off, sk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
-            cv[k] = ld64(c1 + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
-        }
+        for (int k0 = 0; k0 < E; k0 += BATCH) {
+            typename A::Twid kv[BATCH];
+            uint64_t cv[BATCH];
 #pragma unroll
-        for (int k = 0; k < E; ++k) {
-            const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
-            const typename A::elem prod = A::mul(A::from_canon(cv[k], md), kv[k], md);
-            st64(out + off, lo, so, A::canon_acc(A::add(prod, x[k]), md));
+            for (int k = 0; k < BATCH; ++k) {
+                kv[k] = A::key(sk + off, sk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
+                cv[k] = ld64(c1 + off, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
+            }
+#pragma unroll
+            for (int k = 0; k < BATCH; ++k) {
+                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * (k0 + k);
+                const typename A::elem prod = A::mul(A::from_canon(cv[k], md), kv[k], md);
+                st64(out + off, lo, so, A::canon_acc(A::add(prod, x[k0 + k]), md));
+            }
         }
     }
 }
@@ -988,38 +1007,43 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_share(ConvJobs j
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(opaque(smp[k]), 1), md);
         ENG::forward_chained(x, lds, turn, opaque(tl), 0, tb.fwd, md);
-        {
+        constexpr int BATCH = E < 8 ? E : 8;       // key values are requested eight slots at a time, as in Encrypt
+#pragma unroll
+        for (int k0 = 0; k0 < E; k0 += BATCH) {
             // h0: two products per slot, each reduced on its own
-            typename A::Twid kv[E];
+            typename A::Twid kv[BATCH];
 #pragma unroll
-            for (int k = 0; k < E; ++k) kv[k] = A::key(sk + off, sk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
+            for (int k = 0; k < BATCH; ++k)
+                kv[k] = A::key(sk + off, sk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
 #pragma unroll
-            for (int k = 0; k < E; ++k) {
-                const uint64_t cv = ld64(c1 + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
-                x[k] = A::from_canon(A::canon_acc(A::add(A::mul(A::from_canon(cv, md), kv[k], md), x[k]), md), md);
+            for (int k = 0; k < BATCH; ++k) {
+                const uint64_t cv = ld64(c1 + off, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
+                x[k0 + k] = A::from_canon(A::canon_acc(A::add(A::mul(A::from_canon(cv, md), kv[k], md), x[k0 + k]), md), md);
             }
 #pragma unroll
-            for (int k = 0; k < E; ++k) kv[k] = A::key(pk + off, pk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
+            for (int k = 0; k < BATCH; ++k)
+                kv[k] = A::key(pk + off, pk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
 #pragma unroll
-            for (int k = 0; k < E; ++k) {
-                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
-                const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k];
-                st64(out + off, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k]), md));
+            for (int k = 0; k < BATCH; ++k) {
+                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * (k0 + k);
+                const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k0 + k];
+                st64(out + off, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k0 + k]), md));
             }
         }
 #pragma unroll
         for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(opaque(smp[k]), 2), md);
         ENG::forward_chained(x, lds, turn, opaque(tl), 0, tb.fwd, md);
-        {
-            typename A::Twid kv[E];
 #pragma unroll
-            for (int k = 0; k < E; ++k)
-                kv[k] = A::key(pk + 2 * LN + off, pk + 3 * LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
+        for (int k0 = 0; k0 < E; k0 += BATCH) {
+            typename A::Twid kv[BATCH];
 #pragma unroll
-            for (int k = 0; k < E; ++k) {
-                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
-                const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k];
-                st64(stash, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k]), md));
+            for (int k = 0; k < BATCH; ++k)
+                kv[k] = A::key(pk + 2 * LN + off, pk + 3 * LN + off, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
+#pragma unroll
+            for (int k = 0; k < BATCH; ++k) {
+                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * (k0 + k);
+                const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k0 + k];
+                st64(stash, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k0 + k]), md));
             }
         }
     }

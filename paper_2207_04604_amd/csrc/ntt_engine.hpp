@@ -87,6 +87,10 @@ struct Engine {
     }
 
     static_assert(LOGB >= ELOG && LOGB <= LOGN, "bad engine shape");
+    // the same shape (threads, ownership, LDS layout) over another arithmetic: the kernels run their
+    // transforms modulo the plaintext modulus with it
+    template <class B>
+    using Rebind = Engine<B, LOGN_, ELOG_, LOGB_>;
 
     // number of stages of pass p and the window base
     static constexpr int stages(int p) { return p < NPASS - 1 ? ELOG : LOGB - ELOG * (NPASS - 1); }
@@ -260,14 +264,17 @@ struct Engine {
     {
         constexpr int X = PF > PT ? PF : PT;
         constexpr bool INTRA = intra_wave<PF, PT>();
-        uint64_t *wr = lds + slot_base<PF, X>(tid);
-        const uint64_t *rd = lds + slot_base<PT, X>(tid);
+        // the same word layout for 8-byte and 4-byte words (a policy with 4-byte words uses the first half
+        // of the buffer; the padding is conflict-free for either width)
+        typedef typename A::word word;
+        word *wr = (word *)lds + slot_base<PF, X>(tid);
+        const word *rd = (const word *)lds + slot_base<PT, X>(tid);
         if (INTRA) wave_sync(); else if (!FRESH) __syncthreads();      // earlier readers of these words are done
 #pragma unroll
-        for (int k = 0; k < E; ++k) wr[slot_off<PF, X>(k)] = to_bits<A>(x[k]);
+        for (int k = 0; k < E; ++k) wr[slot_off<PF, X>(k)] = to_word<A>(x[k]);
         if (INTRA) wave_sync(); else __syncthreads();
 #pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = from_bits<A>(rd[slot_off<PT, X>(k)]);
+        for (int k = 0; k < E; ++k) x[k] = from_word<A>(rd[slot_off<PT, X>(k)]);
     }
 
     template <int P, bool FRESH = false>
@@ -282,6 +289,8 @@ struct Engine {
             fwd_from<P + 1, FRESH>(x, wn, lds, tid, blk, tw, md);
         } else {
             fwd_pass<P>(x, w, tid, blk, tw, md);
+#pragma unroll
+            for (int k = 0; k < E; ++k) A::fwd_end(x[k], md);
         }
     }
 
@@ -344,6 +353,9 @@ struct Engine {
         if constexpr (P + 1 < NPASS) {
             exchange<P, P + 1, FRESH && P == 0>(x, lds, tid);
             forward<P + 1, FRESH>(x, lds, tid, t, md);
+        } else {
+#pragma unroll
+            for (int k = 0; k < E; ++k) A::fwd_end(x[k], md);
         }
     }
     D2_DEV static void forward_chained(elem (&x)[E], uint64_t *lds, uint32_t &turn, int tid, const Twiddles &t,

@@ -286,12 +286,13 @@ def test_coefficient_form_export_equals_the_oracles_objects(name):
     ctx.close()
 
 
-def test_clamp_with_a_31_bit_plaintext_modulus():
-    """t just below 2^31: the clamp bound is above 2^24 and not a float32; values around it, both packings."""
+def test_clamp_with_a_30_bit_plaintext_modulus():
+    """t just below 2^30 (the largest the library takes): the clamp bound is above 2^24 and not a float32;
+    values around it, both packings."""
     log2n = 10
-    t = O.find_primes(31, log2n, 1)[0]
+    t = O.find_primes(30, log2n, 1)[0]
     cfg = toy_config(log2n, O.find_primes(44, log2n, 2), t, parties=3, n_values=1024 + 9, frac_bits=0)
-    o, ctx, perm = make_pair(cfg, max_group=3)
+    o, ctx, perm = make_pair(cfg, max_group=5)        # floor(((t-1)/2)/5) = 107370700 is not a float32
     clamp = o.encode_clamp()
     assert clamp > (1 << 24) and int(np.float32(clamp)) != clamp
     up = np.nextafter(np.float32(clamp), np.float32(np.inf)) if int(np.float32(clamp)) <= clamp else np.float32(clamp)

@@ -1,5 +1,5 @@
-"""Every (arithmetic back-end, ring degree) pair the library instantiates, against the oracle: the three
-back-ends are chosen by the largest prime (< 2^44, < 2^55, < 2^61), the kernel shapes by log2 N.  The five
+"""Every (arithmetic back-end, ring degree) pair the library instantiates, against the oracle: the four
+back-ends are chosen by the largest prime (< 2^30, < 2^44, < 2^55, < 2^61), the kernel shapes by log2 N.  The five
 benchmark configurations cover five of these pairs; this sweep covers the rest with small seeded inputs
 (two or three ciphertexts, a ragged tail), every intermediate object compared bit for bit."""
 import numpy as np
@@ -14,10 +14,10 @@ from test_gpu_parity import fixed_point_sum, run_calls_and_compare, run_fused
 pytestmark = pytest.mark.gpu
 
 
-# (log2 N, prime bits, limbs); primes "of b bits" lie just below 2^b: 44 bits is the widest the double-precision
-# back-end takes, 45 to 55 go to the second, 56 to 61 to the third.  Small primes come in pairs so that the
+# (log2 N, prime bits, limbs); primes "of b bits" lie just below 2^b: 30 bits is the widest the 32-bit back-end
+# takes, 31 to 44 go to the double-precision one, 45 to 55 to the third, 56 to 61 to the fourth.  Small primes come in pairs so that the
 # plaintext modulus leaves room for the noise.
-SCHEME_SHAPES = [(10, 44, 2), (10, 45, 1), (10, 55, 2), (10, 56, 1), (10, 61, 2), (11, 36, 3), (11, 44, 1), (11, 61, 2),
+SCHEME_SHAPES = [(10, 30, 2), (10, 31, 2), (11, 30, 2), (12, 30, 2), (12, 27, 3), (14, 30, 2), (10, 44, 2), (10, 45, 1), (10, 55, 2), (10, 56, 1), (10, 61, 2), (11, 36, 3), (11, 44, 1), (11, 61, 2),
                  (12, 45, 2), (12, 55, 1), (12, 61, 2), (13, 30, 2), (13, 44, 2), (13, 56, 1), (13, 61, 2), (14, 36, 2),
                  (14, 44, 1), (14, 61, 2)]
 
@@ -39,7 +39,8 @@ def test_round_objects_for_every_backend_and_degree(log2n, bits, L):
 
 
 @pytest.mark.parametrize("log2n,bits,L,batch", [(15, 36, 2, 3), (15, 55, 1, 2), (15, 61, 2, 2), (16, 44, 1, 3), (16, 45, 2, 2),
-                                                (16, 56, 1, 9), (10, 61, 1, 5), (12, 55, 3, 2), (14, 30, 1, 2)])
+                                                (16, 56, 1, 9), (10, 61, 1, 5), (12, 55, 3, 2), (14, 30, 1, 2),
+                                                (15, 30, 2, 3), (16, 30, 1, 9), (16, 31, 1, 2), (10, 20, 1, 2), (13, 24, 2, 2)])
 def test_transforms_for_every_backend_and_degree(log2n, bits, L, batch):
     """Transform-only contexts (t = 0), including the two-kernel path for N > 16384 with batches that do not
     fill a workgroup's share of polynomials."""
