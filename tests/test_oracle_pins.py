@@ -90,6 +90,15 @@ def _python_is_probable_prime(n):
     return True
 
 
+def test_stored_expected_values_are_reproduced_by_their_generator():
+    """tests/golden/params.txt and toy_round.txt are what tests/golden/regenerate.py writes: plain Python integers
+    and the brute-force reference, nothing of the oracle."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(GOLD, "regenerate.py")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr
+
+
 def test_prime_search_reproduces_the_pinned_parameter_sets(orc):
     rows = _rows("params.txt")
     sets = {}
