@@ -353,6 +353,18 @@ struct ArithS {
         x = shoup_tail_add<SC>(y, w.w, qhat_approx<SC>(y, w.ws), m.nq, u);
         y = (2 * u + 4 * m.q) - x;
     }
+    // First stage on small signed inputs (|xv|, |yv| <= 32): w*yv is an exact 64-bit product (|w yv| < 32q
+    // < 2^60), so nothing is reduced: x' = (xv + 32q) + w yv, y' = (xv + 32q) - w yv, both in (0, 64q + 32).
+    // The forward bound becomes 64q + 4q per later stage: 64q + 52q + one lazy product < 128q <= 2^62 for
+    // the longest ring (2^14) and q < 2^55.
+    template <bool SC = false>
+    D2_DEV static void ct_small(int32_t xv, int32_t yv, elem &x, elem &y, const Twid &w, const Mod &m)
+    {
+        const int64_t t = (int64_t)w.w * (int64_t)yv;
+        const uint64_t base = 32 * m.q + (uint64_t)(int64_t)xv;
+        x = base + (uint64_t)t;
+        y = base - (uint64_t)t;
+    }
     D2_DEV static void fwd_pass_begin(elem &, const Mod &) {}
     D2_DEV static void fwd_end(elem &, const Mod &) {}
     // inverse: values in [0, 4q)
@@ -440,6 +452,14 @@ struct ArithB {
         const elem u = csub(x, two_q);
         x = shoup_tail_add<SC>(y, w.w, qhat_exact<SC>(y, w.ws), m.nq, u);       // u + t
         y = (2 * u + two_q) - x;                                                // u + 2q - t
+    }
+    // first stage on small signed inputs: no short cut here (the butterflies need their inputs below 4q)
+    template <bool SC = false>
+    D2_DEV static void ct_small(int32_t xv, int32_t yv, elem &x, elem &y, const Twid &w, const Mod &m)
+    {
+        x = from_small(xv, m);
+        y = from_small(yv, m);
+        ct<SC>(x, y, w, m);
     }
     D2_DEV static void fwd_pass_begin(elem &, const Mod &) {}
     D2_DEV static void fwd_end(elem &, const Mod &) {}
@@ -551,6 +571,16 @@ struct ArithF {
         x = u + t;
         y = u - t;
     }
+    // First stage on small signed inputs (|xv|, |yv| <= 32): w*yv is exact in a double (< 2^49), so the
+    // stage is one multiplication and two additions; the values then reach 32q and, with q/2 more per later
+    // stage and one lazy product, stay below 40q.
+    template <bool SC = false>
+    D2_DEV static void ct_small(int32_t xv, int32_t yv, elem &x, elem &y, const Twid &w, const Mod &)
+    {
+        const double t = w.w * (double)yv, u = (double)xv;
+        x = u + t;
+        y = u - t;
+    }
     D2_DEV static void fwd_pass_begin(elem &, const Mod &) {}
     D2_DEV static void fwd_end(elem &, const Mod &) {}
     template <bool SC = false>
@@ -571,9 +601,9 @@ struct ArithF {
     D2_DEV static void inv_pass_begin(elem &x, const Mod &m) { x = reduce(x, m); }
     D2_DEV static elem inv_input(uint64_t canon, const Mod &) { return u2d(canon); }
 
-    // |x| <= 32 q -> [0, q).  x/q is either an integer or at least 1/q > 2^-44 away from one; the
-    // computed quotient is off by less than 2^-47, so with a bias of 2^-46 floor() is exact and the
-    // remainder needs no correction.
+    // |x| <= 40 q -> [0, q).  x/q is either an integer or at least 1/q > 2^-44 away from one; the
+    // computed quotient is off by less than 2 * 40 * 2^-53 < 2^-46.6 (the rounding of 1/q and of the
+    // fused multiply-add), so with a bias of 2^-46 floor() is exact and the remainder needs no correction.
     D2_DEV static uint64_t canon_wide(elem x, const Mod &m)
     {
         const double b = __builtin_floor(__builtin_fma(x, m.qinv, 0x1p-46));
@@ -649,6 +679,14 @@ struct Arith32 {
         const elem t = mul<SC>(y, w, m);
         x = u + t;
         y = u + m.two_q - t;
+    }
+    // first stage on small signed inputs: no short cut (8 instructions per butterfly as it is)
+    template <bool SC = false>
+    D2_DEV static void ct_small(int32_t xv, int32_t yv, elem &x, elem &y, const Twid &w, const Mod &m)
+    {
+        x = from_small(xv, m);
+        y = from_small(yv, m);
+        ct<SC>(x, y, w, m);
     }
     D2_DEV static void fwd_pass_begin(elem &, const Mod &) {}
     // the last step of a forward transform: [0, 4q) -> [0, 2q)

@@ -605,9 +605,10 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
         constexpr bool STASH = E > 8;
         uint64_t *stash = out + LN + off;
         elem u[E];
+        int32_t sv[E];          // the samples of this transform as plain small integers
 #pragma unroll
-        for (int k = 0; k < E; ++k) u[k] = A::from_small(sbyte(opaque(smp[k]), 0), md);
-        ENG::forward_chained(u, lds, turn, tl, 0, tb.fwd, md);
+        for (int k = 0; k < E; ++k) sv[k] = sbyte(opaque(smp[k]), 0);
+        ENG::forward_chained_small(sv, u, lds, turn, tl, tb.fwd, md);
         if (STASH) {
 #pragma unroll
             for (int k = 0; k < E; ++k) st64(stash, 8u * (uint32_t)tl, 8u * ENG::T * k, to_bits<A>(u[k]));
@@ -634,8 +635,8 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
             }
         }
 #pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(opaque(smp[k]), 2), md);
-        ENG::forward_chained(x, lds, turn, opaque(tl), 0, tb.fwd, md);
+        for (int k = 0; k < E; ++k) sv[k] = sbyte(opaque(smp[k]), 2);
+        ENG::forward_chained_small(sv, x, lds, turn, opaque(tl), tb.fwd, md);
 #pragma unroll
         for (int k0 = 0; k0 < E; k0 += BATCH) {
             typename A::Twid kv[BATCH];
@@ -679,9 +680,10 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_share(ShareJobs jobs, ui
         const size_t off = (size_t)limb * ENG::NB;
         const int tl = opaque(tid);
         typename A::elem x[E];
+        int32_t sv[E];
 #pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = A::from_small(opaque(e[k]), md);
-        ENG::forward_chained(x, lds, turn, tl, 0, tb.fwd, md);
+        for (int k = 0; k < E; ++k) sv[k] = opaque(e[k]);
+        ENG::forward_chained_small(sv, x, lds, turn, tl, tb.fwd, md);
         // key and ciphertext values are requested eight slots at a time: a batch of sixteen (six registers
         // per slot next to the transform's output) does not fit the register budget
         constexpr int BATCH = E < 8 ? E : 8;
@@ -996,17 +998,18 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_share(ConvJobs j
         constexpr bool STASH = E > 8;
         uint64_t *stash = out + LN + off;
         elem u[E];
+        int32_t sv[E];
 #pragma unroll
-        for (int k = 0; k < E; ++k) u[k] = A::from_small(sbyte(opaque(smp[k]), 0), md);
-        ENG::forward_chained(u, lds, turn, tl, 0, tb.fwd, md);
+        for (int k = 0; k < E; ++k) sv[k] = sbyte(opaque(smp[k]), 0);
+        ENG::forward_chained_small(sv, u, lds, turn, tl, tb.fwd, md);
         if (STASH) {
 #pragma unroll
             for (int k = 0; k < E; ++k) st64(stash, 8u * (uint32_t)tl, 8u * ENG::T * k, to_bits<A>(u[k]));
         }
         elem x[E];
 #pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(opaque(smp[k]), 1), md);
-        ENG::forward_chained(x, lds, turn, opaque(tl), 0, tb.fwd, md);
+        for (int k = 0; k < E; ++k) sv[k] = sbyte(opaque(smp[k]), 1);
+        ENG::forward_chained_small(sv, x, lds, turn, opaque(tl), tb.fwd, md);
         constexpr int BATCH = E < 8 ? E : 8;       // key values are requested eight slots at a time, as in Encrypt
 #pragma unroll
         for (int k0 = 0; k0 < E; k0 += BATCH) {
@@ -1031,8 +1034,8 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_share(ConvJobs j
             }
         }
 #pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = A::from_small(sbyte(opaque(smp[k]), 2), md);
-        ENG::forward_chained(x, lds, turn, opaque(tl), 0, tb.fwd, md);
+        for (int k = 0; k < E; ++k) sv[k] = sbyte(opaque(smp[k]), 2);
+        ENG::forward_chained_small(sv, x, lds, turn, opaque(tl), tb.fwd, md);
 #pragma unroll
         for (int k0 = 0; k0 < E; k0 += BATCH) {
             typename A::Twid kv[BATCH];

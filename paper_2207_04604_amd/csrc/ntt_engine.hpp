@@ -170,13 +170,14 @@ struct Engine {
         }
     }
 
-    template <int P>
+    // SKIP_FIRST: the first stage of the pass has been done already (see forward_chained_small)
+    template <int P, bool SKIP_FIRST = false>
     D2_DEV static void fwd_pass(elem (&x)[E], const Twid (&w)[E], int tid, uint32_t blk, const Tw *tw, const Mod &md)
     {
         constexpr int wb = wbase(P), lo = sbit(P), r = stages(P);
         const uint32_t hi = tw_hi<P>(tid);
 #pragma unroll
-        for (int b = lo + r - 1; b >= lo; --b) {           // stage bit inside the block index
+        for (int b = lo + r - 1 - (SKIP_FIRST ? 1 : 0); b >= lo; --b) {           // stage bit inside the block index
             const int kb = b - wb;
             Twid ws[E];
             if constexpr (!ahead<P>()) D2_LOAD_STAGE(ws, 0, b)
@@ -277,18 +278,18 @@ struct Engine {
         for (int k = 0; k < E; ++k) x[k] = from_word<A>(rd[slot_off<PT, X>(k)]);
     }
 
-    template <int P, bool FRESH = false>
+    template <int P, bool FRESH = false, bool SKIP_FIRST = false>
     D2_DEV static void fwd_from(elem (&x)[E], const Twid (&w)[E], uint64_t *lds, int tid, uint32_t blk,
                                 const Tw *tw, const Mod &md)
     {
         if constexpr (P + 1 < NPASS) {
             Twid wn[E];
-            fwd_pass<P>(x, w, tid, blk, tw, md);
+            fwd_pass<P, SKIP_FIRST>(x, w, tid, blk, tw, md);
             load_tw<P + 1, false, true>(wn, tid, blk, tw);
             exchange<P, P + 1, FRESH && P == 0>(x, lds, tid);      // later exchanges meet this transform's own readers
             fwd_from<P + 1, FRESH>(x, wn, lds, tid, blk, tw, md);
         } else {
-            fwd_pass<P>(x, w, tid, blk, tw, md);
+            fwd_pass<P, SKIP_FIRST>(x, w, tid, blk, tw, md);
 #pragma unroll
             for (int k = 0; k < E; ++k) A::fwd_end(x[k], md);
         }
@@ -327,6 +328,24 @@ struct Engine {
         Twid w[E];
         load_tw<0, false, true>(w, tid, blk, tw);
         fwd_from<0, PINGPONG>(x, w, next_buffer(lds, turn), tid, blk, tw, md);
+    }
+
+    // The next forward transform of a chain for a whole polynomial of small signed coefficients
+    // (|v[k]| <= 32: ternary or centred-binomial samples), given as plain integers in pass-0 ownership.
+    // Its first stage multiplies the twiddle by a small number: the policy does that without a modular
+    // reduction and without first mapping the inputs into [0, q) (ct_small); the remaining stages are
+    // the usual ones.  Needs at least two stages in the first pass and a whole-polynomial engine.
+    D2_DEV static void forward_chained_small(const int32_t (&v)[E], elem (&x)[E], uint64_t *lds, uint32_t &turn, int tid,
+                                             const Tw *tw, const Mod &md)
+    {
+        static_assert(LOGB == LOGN && stages(0) >= 2 && ahead<0>(), "shape without a separable first stage");
+        Twid w[E];
+        load_tw<0, false, true>(w, tid, 0, tw);
+        constexpr int kb = ELOG - 1;                      // the first stage pairs slots k and k + E/2, one twiddle
+#pragma unroll
+        for (int j = 0; j < (1 << kb); ++j)
+            A::template ct_small<uniform_tw<0>()>(v[j], v[j | (1 << kb)], x[j], x[j | (1 << kb)], w[tw_slot(kb, 0)], md);
+        fwd_from<0, PINGPONG, true>(x, w, next_buffer(lds, turn), tid, 0, tw, md);
     }
 
     // All twiddles of one transform, for callers that run several transforms with the same table and

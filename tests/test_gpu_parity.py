@@ -311,8 +311,11 @@ def test_clamp_with_a_30_bit_plaintext_modulus():
 
 
 def test_eta_and_small_prime_variants():
-    """eta = 1 and eta = 32 (full words), a 30-bit prime next to 61-bit-class primes."""
-    for (eta, bits, L, log2n) in [(1, 30, 1, 10), (32, 60, 2, 10), (7, 36, 4, 12)]:
+    """eta = 1 and eta = 32 (full words: the largest samples, |e| <= 32, which the reduction-free first stage of
+    the small-input transforms is sized for) on every arithmetic back-end, incl. the longest ring with a prime just
+    below 2^55 and the widest double-precision prime."""
+    for (eta, bits, L, log2n) in [(1, 30, 1, 10), (32, 60, 2, 10), (7, 36, 4, 12), (32, 55, 1, 14), (32, 54, 2, 13),
+                                  (32, 44, 2, 12), (32, 30, 2, 11)]:
         q = O.find_primes(bits, log2n, L)
         cfg = toy_config(log2n, q, 12289 if log2n == 10 else 65537, parties=2, n_values=(1 << log2n) + 3, frac_bits=3)
         cfg.eta = eta
