@@ -720,6 +720,33 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_share(ShareJobs jobs, ui
 // to x in R_t, and the refreshed ciphertext (Lambda x + sum eta1_k, alpha) goes to ct_out.
 // aux: alpha [C][L][N] in evaluation form.
 // -------------------------------------------------------------------------------------
+// One limb's term of round(t y / Q) = round(sum_i t y_i' / q_i): y_i' = y_i (Q/q_i)^-1 mod q_i, then
+// y_i' * theta / 2^128 = integer part, next 64 bits = fraction (theta = floor(t 2^128 / q_i)); added to the
+// running integer part and 64-bit fraction of a coefficient.
+D2_DEV void scale_term(uint64_t y_canon, const LimbTab &tb, uint64_t &acc_int, uint64_t &acc_frac)
+{
+    const uint64_t yi = mul_shoup64(y_canon, tb.gamma.w, tb.gamma.ws, tb.q);
+    uint64_t hi_lo = yi * tb.theta_hi, hi_hi = __umul64hi(yi, tb.theta_hi);
+    uint64_t lo_hi = __umul64hi(yi, tb.theta_lo);
+    uint64_t frac = hi_lo + lo_hi;
+    uint64_t ip = hi_hi + (frac < hi_lo ? 1 : 0);
+    uint64_t nf = acc_frac + frac;
+    acc_int += ip + (nf < frac ? 1 : 0);
+    acc_frac = nf;
+}
+// + 1/2, floor, mod t.  The sum is below (L + 1) t < 2^35: reduced in doubles (exact on integers; the
+// quotient estimate can be off by one in either direction).
+D2_DEV uint32_t round_mod_t(uint64_t acc_int, uint64_t acc_frac, const RoundConst &rc)
+{
+    const double td = (double)(uint32_t)rc.t, tinv = 1.0 / td;
+    const uint64_t v = acc_int + (acc_frac >> 63);
+    const double vd = (double)(uint32_t)v + 4294967296.0 * (double)(uint32_t)(v >> 32);
+    double r = __builtin_fma(-__builtin_floor(vd * tinv), td, vd);
+    r = r < 0.0 ? r + td : r;
+    r = r >= td ? r - td : r;
+    return (uint32_t)r;
+}
+
 enum { COMBINE_COLLECTIVE = 0, COMBINE_CONVERT = 1, COMBINE_BOOTSTRAP = 2 };
 template <class ENG, bool DECODE, int MODE, class SH>
 D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_t K, const uint64_t *aux,
@@ -804,31 +831,11 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
         }
         ENG::template inverse<true>(x, lds, tl, 0, tb.inv, md, A::tw(tb.ninv), A::tw(tb.wn));
 #pragma unroll
-        for (int k = 0; k < E; ++k) {
-            const uint64_t yi = mul_shoup64(A::canon_inv(x[k], md), tb.gamma.w, tb.gamma.ws, q);   // y_i'
-            // yi * theta / 2^128 = integer part, next 64 bits = fraction (theta = floor(t 2^128 / q))
-            uint64_t hi_lo = yi * tb.theta_hi, hi_hi = __umul64hi(yi, tb.theta_hi);
-            uint64_t lo_hi = __umul64hi(yi, tb.theta_lo);
-            uint64_t frac = hi_lo + lo_hi;
-            uint64_t ip = hi_hi + (frac < hi_lo ? 1 : 0);
-            uint64_t nf = acc_frac[k] + frac;
-            acc_int[k] += ip + (nf < frac ? 1 : 0);
-            acc_frac[k] = nf;
-        }
+        for (int k = 0; k < E; ++k) scale_term(A::canon_inv(x[k], md), tb, acc_int[k], acc_frac[k]);
     }
-    // + 1/2, floor, mod t.  The sum is below (L + 1) t < 2^36: reduce it in doubles (exact on
-    // integers; the quotient estimate can be off by one in either direction).
-    const double td = (double)(uint32_t)rc.t, tinv = 1.0 / td;
     uint32_t m[E];
 #pragma unroll
-    for (int k = 0; k < E; ++k) {
-        const uint64_t v = acc_int[k] + (acc_frac[k] >> 63);
-        const double vd = (double)(uint32_t)v + 4294967296.0 * (double)(uint32_t)(v >> 32);
-        double r = __builtin_fma(-__builtin_floor(vd * tinv), td, vd);
-        r = r < 0.0 ? r + td : r;
-        r = r >= td ? r - td : r;
-        m[k] = (uint32_t)r;
-    }
+    for (int k = 0; k < E; ++k) m[k] = round_mod_t(acc_int[k], acc_frac[k], rc);
     if constexpr (MODE == COMBINE_BOOTSTRAP) {
         // x sits where a forward transform takes its input: c0' = NTT(Lambda x) + sum eta1_k, c1' = alpha
         uint64_t *ct_out = pt + (size_t)c * 2 * LN;
