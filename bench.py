@@ -208,6 +208,7 @@ def main():
                 "aggregated_ct_per_s": self.G * C_ / sec,
                 "phase_ms": {"encode_encrypt": phase_ms[0], "aggregate": phase_ms[1], "shares": phase_ms[2],
                              "combine_decode": phase_ms[3]},
+                "phase_roofline": self.phase_roofline(phase_ms),
                 "round_algorithmic": {"GB": round_bytes / 1e9, "GB_per_s": round_bytes / 1e9 / sec,
                                       "frac_hbm_peak": round_bytes / 1e9 / sec / HBM_PEAK_GBS,
                                       "butterfly_Tops_per_s": round_bf * self.opb / sec / 1e12,
@@ -219,6 +220,31 @@ def main():
                               "frac_hbm_peak": enc_bytes / 1e9 / (enc_launch_ms * 1e-3) / HBM_PEAK_GBS,
                               "ops_per_butterfly": self.opb, "arith": self.arith},
             }
+
+        def phase_roofline(self, phase_ms):
+            """Each phase against both rooflines: algorithmic bytes (every message written once and read once) over
+            HBM peak, and butterfly instructions of its transforms over the VALU peak."""
+            N, L, C_ = self.N, self.L, self.C
+            S = 16 * L * N
+            bf = (N // 2) * self.cfg.log2_n
+            ks = [len(g) for g in self.groups]
+            nbytes = {"encode_encrypt": sum(k * (S + 4 * N) for k in ks) * C_,
+                      "aggregate": sum((k + 1) * S for k in ks) * C_,
+                      "shares": sum(k * S for k in ks) * C_,                       # c1 read per member, share written
+                      "combine_decode": sum((k + 1) * S / 2 + 4 * N for k in ks) * C_}
+            # transforms modulo q_i at the context's instruction count, the ones modulo t on 32-bit residues (8)
+            ops = {"encode_encrypt": sum(k * (3 * L * self.opb + 8) for k in ks) * C_ * bf,
+                   "aggregate": 0,
+                   "shares": sum(k * L * self.opb for k in ks) * C_ * bf,
+                   "combine_decode": len(ks) * (L * self.opb + 8) * C_ * bf}
+            out = {}
+            for name, ms in zip(("encode_encrypt", "aggregate", "shares", "combine_decode"), phase_ms):
+                sec = ms * 1e-3
+                out[name] = {"algorithmic_GB_per_s": nbytes[name] / 1e9 / sec,
+                             "frac_hbm_peak": nbytes[name] / 1e9 / sec / HBM_PEAK_GBS,
+                             "butterfly_Tops_per_s": ops[name] / sec / 1e12,
+                             "frac_valu_peak": ops[name] / sec / 1e12 / VALU_PEAK_TOPS}
+            return out
 
         def close(self):
             self.ctx.close()
@@ -289,6 +315,7 @@ def main():
                           f"then {P} key shares and {G} collective public keys on the GPU",
                   "create_ms": w.create_ms, "keys_ms": w.keys_ms},
         "phase_ms": fig["phase_ms"],
+        "phase_roofline": fig["phase_roofline"],
         "phase_ms_from": f"{nph} further steps with an event after every phase (of the timed steps every "
                          f"{EVENT_EVERY}th records two events, around the dominant kernel's launches)",
         "round_algorithmic": fig["round_algorithmic"],

@@ -51,7 +51,11 @@ def test_parameter_validation(lib):
         _params(q=((1 << 61) + 20 * 2048 + 1,)),           # above 2^61
         _params(t=12290), _params(t=1073707009),           # t not prime-congruent / t >= q
         _params(eta=0), _params(eta=33), _params(f=31), _params(kmax=0),
+        # a 31-bit prime t = 1 mod 2N below a 36-bit prime q: valid BFV, above the library's t < 2^30
+        _params(q=(68719464449,), t=2147473409),
     ]
+    ok36, keep36 = _params(q=(68719464449,), t=1073707009)   # the same shape with a 30-bit t is accepted
+    assert B.workspace_bytes(ok36) > 0
     for prm, keep2 in bad:
         assert B.workspace_bytes(prm) == 0
         handle = C.c_void_p()
@@ -119,3 +123,25 @@ def test_grouping_merges_identical_neighbourhoods():
     adj = [[1, 2], [0, 2], [0, 1], [4], [3]]
     groups, owner = closed_neighbourhood_groups(adj)
     assert groups == [[0, 1, 2], [3, 4]] and owner == [0, 0, 0, 1, 1]
+
+
+def test_bench_reads_kernel_traffic_from_the_committed_profiles():
+    """bench.py takes roofline.traffic from the rocprofv3 summaries under profiles/: every round configuration it
+    times by default has a k_encrypt line there, the C5 leg its four kernels, and unknown kernels give None."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    for wl in ("C2", "C3", "C4"):
+        got = bench.profiled_traffic(wl, "k_encrypt")
+        assert got is not None and got[0] > 0 and got[1] > 0 and got[2].startswith("profiles/")
+        cfg = CONFIGS[wl]
+        jobs = sum(len(g) for g in cfg.groups())
+        launches = -(-jobs // bench.JOBS_PER_LAUNCH)
+        written = jobs * cfg.C * 16 * cfg.L * cfg.N / launches          # the ciphertexts of one launch
+        assert written <= got[1] <= 2.0 * written, (wl, got, written)
+    for k in ("k_head_forward", "k_tail_forward", "k_tail_inverse", "k_head_inverse"):
+        rd, wr, _ = bench.profiled_traffic("C5", k)
+        assert 0.95 * 2 ** 29 <= wr <= 1.1 * 2 ** 29 and rd >= 0.95 * 2 ** 29
+    assert bench.profiled_traffic("C3", "k_no_such_kernel") is None
+    assert bench.ops_per_butterfly(1 << 29)[0] == 8 and bench.ops_per_butterfly((1 << 54) - 1)[0] == 15
