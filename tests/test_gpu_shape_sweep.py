@@ -59,3 +59,39 @@ def test_transforms_for_every_backend_and_degree(log2n, bits, L, batch):
     ctx.ntt_inverse(d, batch)
     assert np.array_equal(to_host(d, polys.shape), polys), "inverse transform"
     ctx.close()
+
+
+# every (back-end, ring degree) pair once: 30 bits -> 32-bit words, 44 -> doubles, 55 -> lazy 64-bit, 61 -> Harvey
+EXTREME_SHAPES = [(log2n, bits) for log2n in range(10, 17) for bits in (30, 44, 55, 61)]
+
+
+@pytest.mark.parametrize("log2n,bits", EXTREME_SHAPES)
+def test_transforms_of_extreme_polynomials(log2n, bits):
+    """Inputs that drive the lazily reduced butterflies to the top of their ranges: every coefficient q - 1, a
+    single q - 1 at either end, alternating q - 1 and 0, all ones, and q - 1 on a random half.  Forward: coefficient
+    form in, compared with the oracle's transform.  Inverse: the same patterns taken as evaluation-form data in the
+    library's layout, compared with the oracle's inverse transform of the values put in natural order."""
+    N = 1 << log2n
+    (q,) = O.find_primes(bits, log2n, 1)
+    o = O.Oracle(log2n, [q], 0, 21, 0, 1, 5)
+    ctx = make_ctx(log2n, [q], 0, seed=5)
+    perm = ctx.index_map()
+    rng = np.random.default_rng(log2n * 100 + bits)
+    pats = np.zeros((6, 1, N), dtype=np.uint64)
+    pats[0] = q - 1
+    pats[1, 0, 0] = q - 1
+    pats[2, 0, N - 1] = q - 1
+    pats[3, 0, ::2] = q - 1
+    pats[4] = 1
+    pats[5, 0, rng.random(N) < 0.5] = q - 1
+    d = to_dev(pats.reshape(-1))
+    ctx.ntt_forward(d, 6)
+    assert np.array_equal(to_host(d, pats.shape), to_eval(o, perm, pats)), "forward transform"
+    d = to_dev(pats.reshape(-1))
+    ctx.ntt_inverse(d, 6)
+    got = to_host(d, pats.shape)
+    for b in range(6):
+        natural = np.zeros(N, dtype=np.uint64)
+        natural[perm] = pats[b, 0]                 # position p of the layout holds evaluation perm[p]
+        assert np.array_equal(got[b, 0], O.ntt_inverse(natural, q, o.psi[0])), f"inverse transform, pattern {b}"
+    ctx.close()
