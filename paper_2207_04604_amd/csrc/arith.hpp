@@ -549,7 +549,10 @@ struct ArithF {
         const double b = __builtin_rint(x * m.qinv);
         return __builtin_fma(-b, m.q, x);
     }
-    // w*y mod q as a signed representative of magnitude <= q/2 + 1, for |w y| < 2^96
+    // w*y mod q as a signed representative, for |w y| < 2^96.  Its magnitude is at most
+    // q/2 + 1.5 |w y| 2^-52: the quotient is rounded from h/q computed with a relative error of 2^-52, and
+    // the low part l of the product (|l| <= |w y| 2^-53) is added after the reduction.  That is q/2 + 1 for
+    // canonical operands and up to 0.75 q for |y| = 42 q at the largest modulus.
     template <bool SC = false>
     D2_DEV static elem mul(elem y, const Twid &w, const Mod &m)
     {
@@ -572,8 +575,10 @@ struct ArithF {
         y = u - t;
     }
     // First stage on small signed inputs (|xv|, |yv| <= 32): w*yv is exact in a double (< 2^49), so the
-    // stage is one multiplication and two additions; the values then reach 32q and, with q/2 more per later
-    // stage and one lazy product, stay below 40q.
+    // stage is one multiplication and two additions.  The values then reach 32q; every later stage adds one
+    // product (see mul), i.e. takes a bound of c q to (1 + 1.5 q 2^-52) c q + q/2: 41.3 q after the 13 further
+    // stages of the longest ring that starts this way (2^14) at q = 2^44, 42.1 q with one more lazy product
+    // on top -- inside what canon_wide accepts (64 q) and far inside the 2^53 of exact integers.
     template <bool SC = false>
     D2_DEV static void ct_small(int32_t xv, int32_t yv, elem &x, elem &y, const Twid &w, const Mod &)
     {
@@ -601,8 +606,8 @@ struct ArithF {
     D2_DEV static void inv_pass_begin(elem &x, const Mod &m) { x = reduce(x, m); }
     D2_DEV static elem inv_input(uint64_t canon, const Mod &) { return u2d(canon); }
 
-    // |x| <= 40 q -> [0, q).  x/q is either an integer or at least 1/q > 2^-44 away from one; the
-    // computed quotient is off by less than 2 * 40 * 2^-53 < 2^-46.6 (the rounding of 1/q and of the
+    // |x| <= 64 q -> [0, q).  x/q is either an integer or at least 1/q > 2^-44 away from one; the
+    // computed quotient is off by at most 2 * 64 * 2^-53 = 2^-46 (the rounding of 1/q and of the
     // fused multiply-add), so with a bias of 2^-46 floor() is exact and the remainder needs no correction.
     D2_DEV static uint64_t canon_wide(elem x, const Mod &m)
     {

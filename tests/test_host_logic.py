@@ -145,3 +145,17 @@ def test_bench_reads_kernel_traffic_from_the_committed_profiles():
         assert 0.95 * 2 ** 29 <= wr <= 1.1 * 2 ** 29 and rd >= 0.95 * 2 ** 29
     assert bench.profiled_traffic("C3", "k_no_such_kernel") is None
     assert bench.ops_per_butterfly(1 << 29)[0] == 8 and bench.ops_per_butterfly((1 << 54) - 1)[0] == 15
+
+
+def test_arithmetic_policies_hold_their_contracts_on_the_host(tmp_path):
+    """The modular-arithmetic header of the kernels, built for the host (its plain-C side, the same formulas the
+    device code pins with assembly) and checked against 128-bit integers on the ends of every documented range:
+    tests/arith_host_check.cpp."""
+    import shutil
+    import subprocess
+    cxx = shutil.which("amdclang++") or "/opt/rocm/llvm/bin/clang++"
+    exe = str(tmp_path / "arith_host_check")
+    subprocess.check_call([cxx, "-O2", "-std=c++17", "-w", "-o", exe, os.path.join(ROOT, "tests", "arith_host_check.cpp")])
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert run.returncode == 0, run.stdout[-2000:]
+    assert "all arithmetic policies hold their contracts" in run.stdout
