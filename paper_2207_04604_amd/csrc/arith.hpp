@@ -337,12 +337,25 @@ struct ArithS {
     {
         return shoup_tail<SC>(y, w.w, qhat_approx<SC>(y, w.ws), m.nq);
     }
+    // w*y mod q in [0, 4q) for a 32-bit y (a plaintext coefficient): with y's high word zero the
+    // quotient estimate is one partial product (s1 y >> 31 < 2^32, at most 2 too small as in mul) and the
+    // tail loses its y1 and h1 terms: 7 instructions instead of 12.
+    D2_DEV static elem mul_u32(uint32_t y, const Twid &w, const Mod &m)
+    {
+        const uint32_t h = (uint32_t)(mul32(hi32(w.ws), y) >> 31);
+        const uint64_t acc = mul32(lo32(w.w), y) + mul32(h, lo32(m.nq));
+        const uint32_t cross = hi32(w.w) * y + h * hi32(m.nq);
+        return acc + ((uint64_t)cross << 32);
+    }
     D2_DEV static elem from_small(int32_t v, const Mod &m)
     {
         return v >= 0 ? (uint64_t)v : m.q - (uint64_t)(uint32_t)(-v);
     }
     D2_DEV static elem from_canon(uint64_t v, const Mod &) { return v; }
     D2_DEV static elem add(elem a, elem b) { return a + b; }
+    // x + v for a small signed v (|v| <= 32), as a forward input: q is added instead of mapping v into
+    // [0, q) first (the forward range has room for it)
+    D2_DEV static elem add_small(elem x, int32_t v, const Mod &m) { return x + (m.q + (uint64_t)(int64_t)v); }
 
     // forward: no correction; each stage adds at most 4q to the bound.
     // x' = u + t comes out of the multiply-add chain itself, y' = u + 4q - t = (2u + 4q) - x'.
@@ -443,6 +456,8 @@ struct ArithB {
     }
     D2_DEV static elem from_canon(uint64_t v, const Mod &) { return v; }
     D2_DEV static elem add(elem a, elem b) { return a + b; }
+    D2_DEV static elem mul_u32(uint32_t y, const Twid &w, const Mod &m) { return mul(y, w, m); }
+    D2_DEV static elem add_small(elem x, int32_t v, const Mod &m) { return x + from_small(v, m); }
 
     // x, y in [0, 4q) -> [0, 4q)
     template <bool SC = false>
@@ -564,6 +579,8 @@ struct ArithF {
     }
     D2_DEV static elem from_small(int32_t v, const Mod &) { return (double)v; }
     D2_DEV static elem from_canon(uint64_t v, const Mod &) { return u2d(v); }
+    D2_DEV static elem mul_u32(uint32_t y, const Twid &w, const Mod &m) { return mul((double)y, w, m); }
+    D2_DEV static elem add_small(elem x, int32_t v, const Mod &) { return x + (double)v; }
     D2_DEV static elem add(elem a, elem b) { return a + b; }
 
     template <bool SC = false>
@@ -675,6 +692,8 @@ struct Arith32 {
     D2_DEV static elem from_small(int32_t v, const Mod &m) { return v >= 0 ? (uint32_t)v : m.q - (uint32_t)(-v); }
     D2_DEV static elem from_canon(uint64_t v, const Mod &) { return (uint32_t)v; }
     D2_DEV static elem add(elem a, elem b) { return a + b; }
+    D2_DEV static elem mul_u32(uint32_t y, const Twid &w, const Mod &m) { return mul(y, w, m); }
+    D2_DEV static elem add_small(elem x, int32_t v, const Mod &m) { return x + from_small(v, m); }
 
     // x, y in [0, 4q) -> [0, 4q)
     template <bool SC = false>

@@ -543,6 +543,64 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_keygen(uint32_t party, u
 }
 
 // -------------------------------------------------------------------------------------
+// dst = u * key + x, canonical, for the E slots of a thread (evaluation form, one limb).  u comes
+// from registers (SRC_REGS: the lazy output of a transform), from raw bits parked at `src`
+// (SRC_PARKED: such an output written out earlier; `src` may be `dst` itself) or from canonical
+// words at `src` (SRC_CANON: a ciphertext component); x is a transform's lazy output; the key is a
+// prepared polynomial (values kp, quotients kps).
+// The order of the memory instructions is written out.  A wait for vector memory counts loads and
+// stores together, in issue order: a load issued after a store cannot be waited for without also
+// waiting for that store to reach memory, and the compiler never moves a load in front of a store
+// that might alias it.  So the slots go in batches (sixteen key values and source words at once
+// exceed the register budget), and the loads of a batch are issued before the stores of the
+// previous one.
+// -------------------------------------------------------------------------------------
+// NEG: dst = x - u * key instead.
+enum { SRC_REGS = 0, SRC_PARKED = 1, SRC_CANON = 2 };
+template <class ENG, int SRC, bool NEG = false>
+D2_DEV void mul_add_store(uint64_t *dst, const uint64_t *kp, const uint64_t *kps, const uint64_t *src,
+                          const typename ENG::A::elem (&u)[ENG::E], const typename ENG::A::elem (&x)[ENG::E], int tl,
+                          const typename ENG::A::Mod &md, uint64_t q = 0 /* the modulus, for NEG */)
+{
+    typedef typename ENG::A A;
+    constexpr int E = ENG::E, BATCH = E < 8 ? E : 8, NB = E / BATCH;
+    const uint32_t lo = 8u * (uint32_t)tl;
+    typename A::Twid kv[BATCH];
+    uint64_t ub[BATCH];
+#pragma unroll
+    for (int k = 0; k < BATCH; ++k) {
+        kv[k] = A::key(kp, kps, lo, 8u * ENG::T * k);
+        if constexpr (SRC != SRC_REGS) ub[k] = ld64(src, lo, 8u * ENG::T * k);
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        uint64_t r[BATCH];
+#pragma unroll
+        for (int k = 0; k < BATCH; ++k) {
+            typename A::elem uu;
+            if constexpr (SRC == SRC_PARKED) uu = from_bits<A>(ub[k]);
+            else if constexpr (SRC == SRC_CANON) uu = A::from_canon(ub[k], md);
+            else uu = u[b * BATCH + k];
+            if constexpr (NEG) {
+                const uint64_t prod = A::canon_acc(A::mul(uu, kv[k], md), md);
+                r[k] = A::canon_acc(A::add(x[b * BATCH + k], A::from_canon(prod ? q - prod : 0, md)), md);
+            } else {
+                r[k] = A::canon_acc(A::add(A::mul(uu, kv[k], md), x[b * BATCH + k]), md);
+            }
+        }
+        if (b + 1 < NB) {
+#pragma unroll
+            for (int k = 0; k < BATCH; ++k) {
+                kv[k] = A::key(kp, kps, lo, 8u * ENG::T * ((b + 1) * BATCH + k));
+                if constexpr (SRC != SRC_REGS) ub[k] = ld64(src, lo, 8u * ENG::T * ((b + 1) * BATCH + k));
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < BATCH; ++k) st64(dst, lo, 8u * ENG::T * (b * BATCH + k), r[k]);
+    }
+}
+
+// -------------------------------------------------------------------------------------
 // BFV.Encrypt in evaluation form.  grid = (C, jobs); one workgroup per ciphertext.
 //   c0 = NTT(Lambda m + e0) + NTT(mu) * p0,   c1 = NTT(e1) + NTT(mu) * p1.
 // FROM_FLOAT: the plaintext is encoded on the fly from the member's gradient;
@@ -616,39 +674,13 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_encrypt(EncJobs jobs, ui
         elem x[E];
 #pragma unroll
         for (int k = 0; k < E; ++k)
-            x[k] = A::add(A::mul(A::from_canon((uint64_t)opaque(m[k]), md), lam, md),
-                          A::from_small(sbyte(opaque(smp[k]), 1), md));
+            x[k] = A::add_small(A::mul_u32(opaque(m[k]), lam, md), sbyte(opaque(smp[k]), 1), md);
         ENG::forward_chained(x, lds, turn, opaque(tl), 0, tb.fwd, md);
-        // the key values are requested in batches of eight slots (a load placed after a store of the
-        // previous slot could not be moved in front of it; sixteen at once exceed the register budget)
-        constexpr int BATCH = E < 8 ? E : 8;
-#pragma unroll
-        for (int k0 = 0; k0 < E; k0 += BATCH) {
-            typename A::Twid kv[BATCH];
-#pragma unroll
-            for (int k = 0; k < BATCH; ++k) kv[k] = A::key(p0, p0s, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
-#pragma unroll
-            for (int k = 0; k < BATCH; ++k) {
-                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * (k0 + k);
-                const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k0 + k];
-                st64(out + off, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k0 + k]), md));
-            }
-        }
+        mul_add_store<ENG, STASH ? SRC_PARKED : SRC_REGS>(out + off, p0, p0s, stash, u, x, tl, md);
 #pragma unroll
         for (int k = 0; k < E; ++k) sv[k] = sbyte(opaque(smp[k]), 2);
         ENG::forward_chained_small(sv, x, lds, turn, opaque(tl), tb.fwd, md);
-#pragma unroll
-        for (int k0 = 0; k0 < E; k0 += BATCH) {
-            typename A::Twid kv[BATCH];
-#pragma unroll
-            for (int k = 0; k < BATCH; ++k) kv[k] = A::key(p1, p1s, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
-#pragma unroll
-            for (int k = 0; k < BATCH; ++k) {
-                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * (k0 + k);
-                const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k0 + k];
-                st64(stash, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k0 + k]), md));
-            }
-        }
+        mul_add_store<ENG, STASH ? SRC_PARKED : SRC_REGS>(stash, p1, p1s, stash, u, x, tl, md);
     }
 }
 
@@ -684,25 +716,7 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_share(ShareJobs jobs, ui
 #pragma unroll
         for (int k = 0; k < E; ++k) sv[k] = opaque(e[k]);
         ENG::forward_chained_small(sv, x, lds, turn, tl, tb.fwd, md);
-        // key and ciphertext values are requested eight slots at a time: a batch of sixteen (six registers
-        // per slot next to the transform's output) does not fit the register budget
-        constexpr int BATCH = E < 8 ? E : 8;
-#pragma unroll
-        for (int k0 = 0; k0 < E; k0 += BATCH) {
-            typename A::Twid kv[BATCH];
-            uint64_t cv[BATCH];
-#pragma unroll
-            for (int k = 0; k < BATCH; ++k) {
-                kv[k] = A::key(sk + off, sk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
-                cv[k] = ld64(c1 + off, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
-            }
-#pragma unroll
-            for (int k = 0; k < BATCH; ++k) {
-                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * (k0 + k);
-                const typename A::elem prod = A::mul(A::from_canon(cv[k], md), kv[k], md);
-                st64(out + off, lo, so, A::canon_acc(A::add(prod, x[k0 + k]), md));
-            }
-        }
+        mul_add_store<ENG, SRC_CANON>(out + off, sk + off, sk + LN + off, c1 + off, x, x, tl, md);
     }
 }
 
@@ -849,7 +863,7 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
             const int tl = opaque(tid);
             typename A::elem x[E];
 #pragma unroll
-            for (int k = 0; k < E; ++k) x[k] = A::mul(A::from_canon((uint64_t)opaque(m[k]), md), lam, md);
+            for (int k = 0; k < E; ++k) x[k] = A::mul_u32(opaque(m[k]), lam, md);
             ENG::forward(x, lds, tl, 0, tb.fwd, md);
             uint64_t y[E], hv[E];
 #pragma unroll
@@ -1017,45 +1031,26 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_convert_share(ConvJobs j
 #pragma unroll
         for (int k = 0; k < E; ++k) sv[k] = sbyte(opaque(smp[k]), 1);
         ENG::forward_chained_small(sv, x, lds, turn, opaque(tl), tb.fwd, md);
-        constexpr int BATCH = E < 8 ? E : 8;       // key values are requested eight slots at a time, as in Encrypt
+        // h0: two products per slot, each reduced on its own; first x <- s c1 + x (loads only, eight slots at a time)
+        constexpr int BATCH = E < 8 ? E : 8;
 #pragma unroll
         for (int k0 = 0; k0 < E; k0 += BATCH) {
-            // h0: two products per slot, each reduced on its own
             typename A::Twid kv[BATCH];
+            uint64_t cv[BATCH];
 #pragma unroll
-            for (int k = 0; k < BATCH; ++k)
+            for (int k = 0; k < BATCH; ++k) {
                 kv[k] = A::key(sk + off, sk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
-#pragma unroll
-            for (int k = 0; k < BATCH; ++k) {
-                const uint64_t cv = ld64(c1 + off, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
-                x[k0 + k] = A::from_canon(A::canon_acc(A::add(A::mul(A::from_canon(cv, md), kv[k], md), x[k0 + k]), md), md);
+                cv[k] = ld64(c1 + off, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
             }
 #pragma unroll
             for (int k = 0; k < BATCH; ++k)
-                kv[k] = A::key(pk + off, pk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
-#pragma unroll
-            for (int k = 0; k < BATCH; ++k) {
-                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * (k0 + k);
-                const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k0 + k];
-                st64(out + off, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k0 + k]), md));
-            }
+                x[k0 + k] = A::from_canon(A::canon_acc(A::add(A::mul(A::from_canon(cv[k], md), kv[k], md), x[k0 + k]), md), md);
         }
+        mul_add_store<ENG, STASH ? SRC_PARKED : SRC_REGS>(out + off, pk + off, pk + LN + off, stash, u, x, tl, md);
 #pragma unroll
         for (int k = 0; k < E; ++k) sv[k] = sbyte(opaque(smp[k]), 2);
         ENG::forward_chained_small(sv, x, lds, turn, opaque(tl), tb.fwd, md);
-#pragma unroll
-        for (int k0 = 0; k0 < E; k0 += BATCH) {
-            typename A::Twid kv[BATCH];
-#pragma unroll
-            for (int k = 0; k < BATCH; ++k)
-                kv[k] = A::key(pk + 2 * LN + off, pk + 3 * LN + off, 8u * (uint32_t)tl, 8u * ENG::T * (k0 + k));
-#pragma unroll
-            for (int k = 0; k < BATCH; ++k) {
-                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * (k0 + k);
-                const elem uu = STASH ? from_bits<A>(ld64(stash, lo, so)) : u[k0 + k];
-                st64(stash, lo, so, A::canon_acc(A::add(A::mul(uu, kv[k], md), x[k0 + k]), md));
-            }
-        }
+        mul_add_store<ENG, STASH ? SRC_PARKED : SRC_REGS>(stash, pk + 2 * LN + off, pk + 3 * LN + off, stash, u, x, tl, md);
     }
 }
 
@@ -1162,39 +1157,19 @@ __global__ void __launch_bounds__(ENG::T, ENG::WAVES) k_bootstrap_share(ConvJobs
         const int tl = opaque(tid);
         uint64_t lm[E];                                     // Lambda M mod q, canonical
 #pragma unroll
-        for (int k = 0; k < E; ++k) lm[k] = A::canon_acc(A::mul(A::from_canon((uint64_t)opaque(mv[k]), md), lam, md), md);
+        for (int k = 0; k < E; ++k) lm[k] = A::canon_acc(A::mul_u32(opaque(mv[k]), lam, md), md);
         elem x[E];
 #pragma unroll
         for (int k = 0; k < E; ++k)
             x[k] = A::add(A::from_canon(lm[k] ? q - lm[k] : 0, md), A::from_small(sbyte(opaque(ev[k]), 0), md));
         ENG::forward_chained(x, lds, turn, tl, 0, tb.fwd, md);
-        {
-            typename A::Twid kv[E];
-#pragma unroll
-            for (int k = 0; k < E; ++k) kv[k] = A::key(sk + off, sk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
-#pragma unroll
-            for (int k = 0; k < E; ++k) {
-                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
-                const uint64_t cv = ld64(c1 + off, lo, so);
-                st64(out + off, lo, so, A::canon_acc(A::add(A::mul(A::from_canon(cv, md), kv[k], md), x[k]), md));
-            }
-        }
+        mul_add_store<ENG, SRC_CANON>(out + off, sk + off, sk + LN + off, c1 + off, x, x, tl, md);
 #pragma unroll
         for (int k = 0; k < E; ++k)
             x[k] = A::add(A::from_canon(lm[k], md), A::from_small(sbyte(opaque(ev[k]), 1), md));
         ENG::forward_chained(x, lds, turn, opaque(tl), 0, tb.fwd, md);
-        {
-            typename A::Twid kv[E];
-#pragma unroll
-            for (int k = 0; k < E; ++k) kv[k] = A::key(sk + off, sk + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
-#pragma unroll
-            for (int k = 0; k < E; ++k) {
-                const uint32_t lo = 8u * (uint32_t)tl, so = 8u * ENG::T * k;
-                const uint64_t av = ld64(alpha + off, lo, so);
-                const uint64_t prod = A::canon_acc(A::mul(A::from_canon(av, md), kv[k], md), md);   // s_k alpha
-                st64(out + LN + off, lo, so, A::canon_acc(A::add(x[k], A::from_canon(prod ? q - prod : 0, md)), md));
-            }
-        }
+        // eta1 = Lambda M + e1 - s_k alpha
+        mul_add_store<ENG, SRC_CANON, true>(out + LN + off, sk + off, sk + LN + off, alpha + off, x, x, tl, md, q);
     }
 }
 

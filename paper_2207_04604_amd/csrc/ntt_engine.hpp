@@ -45,6 +45,14 @@ D2_DEV void wave_sync()
 #endif
 }
 
+// A line the instruction scheduler moves nothing across (no instruction of its own).
+D2_DEV void sched_fence()
+{
+#if D2_GCN_ASM
+    __builtin_amdgcn_sched_barrier(0);
+#endif
+}
+
 // table entry with an index that is uniform over the workgroup
 template <class A>
 D2_DEV typename A::Twid load_tw_uniform(const Tw *tw, uint32_t i)
@@ -176,11 +184,20 @@ struct Engine {
     {
         constexpr int wb = wbase(P), lo = sbit(P), r = stages(P);
         const uint32_t hi = tw_hi<P>(tid);
+        // Twiddles that are not fetched as a set (see ahead) are requested one stage ahead: those of the
+        // next stage go out before the butterflies of this one, into the other of two small buffers.
+        constexpr int first = lo + r - 1 - (SKIP_FIRST ? 1 : 0);
+        Twid ws[2][E / 2 > 0 ? E / 2 : 1];
+        if constexpr (!ahead<P>()) D2_LOAD_STAGE(ws[first & 1], 0, first)
 #pragma unroll
-        for (int b = lo + r - 1 - (SKIP_FIRST ? 1 : 0); b >= lo; --b) {           // stage bit inside the block index
+        for (int b = first; b >= lo; --b) {           // stage bit inside the block index
             const int kb = b - wb;
-            Twid ws[E];
-            if constexpr (!ahead<P>()) D2_LOAD_STAGE(ws, 0, b)
+            if constexpr (!ahead<P>()) {
+                if (b > lo) {
+                    D2_LOAD_STAGE(ws[(b - 1) & 1], 0, b - 1)
+                    sched_fence();      // or the compiler moves the requests down to their first use
+                }
+            }
 #pragma unroll
             for (int g = 0; g < (E >> (kb + 1)); ++g) {    // distinct twiddles of this stage
 #pragma unroll
@@ -189,7 +206,7 @@ struct Engine {
                     if constexpr (ahead<P>())
                         A::template ct<uniform_tw<P>()>(x[k0], x[k0 | (1 << kb)], w[tw_slot(kb, g)], md);
                     else
-                        A::template ct<uniform_tw<P>()>(x[k0], x[k0 | (1 << kb)], ws[g], md);
+                        A::template ct<uniform_tw<P>()>(x[k0], x[k0 | (1 << kb)], ws[b & 1][g], md);
                 }
             }
         }
@@ -208,15 +225,24 @@ struct Engine {
 #pragma unroll
             for (int k = 0; k < E; ++k) A::inv_pass_begin(x[k], md);
         }
+        // stage-by-stage twiddles: one stage ahead, as in fwd_pass (the first stage's are requested here)
+        Twid ws[2][E / 2 > 0 ? E / 2 : 1];
+        if constexpr (!ahead<P>()) {
+            if (!(FOLD && lo == LOGN - 1)) D2_LOAD_STAGE(ws[lo & 1], 0, lo)
+        }
 #pragma unroll
         for (int b = lo; b < lo + r; ++b) {
             const int kb = b - wb;
+            if constexpr (!ahead<P>()) {
+                if (b + 1 < lo + r && !(FOLD && b + 1 == LOGN - 1)) {
+                    D2_LOAD_STAGE(ws[(b + 1) & 1], 0, b + 1)
+                    sched_fence();
+                }
+            }
             if (FOLD && b == LOGN - 1) {
 #pragma unroll
                 for (int j = 0; j < (1 << kb); ++j) A::template gs_last<true>(x[j], x[j | (1 << kb)], ninv, wn, md);
             } else {
-                Twid ws[E];
-                if constexpr (!ahead<P>()) D2_LOAD_STAGE(ws, 0, b)
 #pragma unroll
                 for (int g = 0; g < (E >> (kb + 1)); ++g) {
 #pragma unroll
@@ -225,7 +251,7 @@ struct Engine {
                         if constexpr (ahead<P>())
                             A::template gs<uniform_tw<P>()>(x[k0], x[k0 | (1 << kb)], w[tw_slot(kb, g)], md);
                         else
-                            A::template gs<uniform_tw<P>()>(x[k0], x[k0 | (1 << kb)], ws[g], md);
+                            A::template gs<uniform_tw<P>()>(x[k0], x[k0 | (1 << kb)], ws[b & 1][g], md);
                     }
                 }
             }

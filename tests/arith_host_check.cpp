@@ -90,6 +90,11 @@ static void check_u64(const char *name, uint64_t q, uint64_t in_mul, uint64_t in
             CHECK(r < prod_q * q && r % q == (uint64_t)(((u128)w * y) % q), "%s mul q=%llu w=%llu y=%llu -> %llu", name,
                   (unsigned long long)q, (unsigned long long)w, (unsigned long long)y, (unsigned long long)r);
         }
+        for (uint64_t y : probes(1ull << 32, q, 300)) {                    // a 32-bit operand (plaintext coefficient)
+            const uint64_t r = A::mul_u32((uint32_t)y, tw, md);
+            CHECK(r < prod_q * q && r % q == (uint64_t)(((u128)w * y) % q), "%s mul_u32 q=%llu w=%llu y=%llu -> %llu", name,
+                  (unsigned long long)q, (unsigned long long)w, (unsigned long long)y, (unsigned long long)r);
+        }
         // forward butterfly
         for (uint64_t x0 : probes(in_fwd, q, 40))
             for (uint64_t y0 : probes(in_fwd, q, 12)) {
@@ -138,6 +143,11 @@ static void check_u64(const char *name, uint64_t q, uint64_t in_mul, uint64_t in
     for (uint64_t x : probes(in_inv_q * q, q, 20000)) CHECK(A::canon_inv(x, md) == x % q, "%s canon_inv %llu", name, (unsigned long long)x);
     for (uint64_t x : probes(fwd_grows ? wide : in_fwd, q, 20000)) CHECK(A::canon_fwd(x, md) == x % q, "%s canon_fwd %llu", name, (unsigned long long)x);
     for (int v = -40; v <= 40; ++v) CHECK(A::from_small(v, md) == mod_of(v, q), "%s from_small %d", name, v);
+    for (int v = -32; v <= 32; ++v)
+        for (uint64_t x : probes(prod_q * q, q, 50)) {
+            const uint64_t r = A::add_small(x, v, md);
+            CHECK(r % q == mod_of((i128)x + v, q) && r < (prod_q + 1) * q + 33, "%s add_small %llu %d", name, (unsigned long long)x, v);
+        }
 }
 
 // ------------------------------------------------------------------ 32-bit residues
@@ -160,6 +170,10 @@ static void check_32(uint64_t q64)
         for (uint32_t y : p32((uint64_t)1 << 32, 2000)) {
             const uint32_t r = A::mul(y, tw, md);
             CHECK(r < 2 * (uint64_t)q && r % q == (uint32_t)(((uint64_t)w * y) % q), "Arith32 mul q=%u w=%u y=%u -> %u", q, w, y, r);
+        }
+        for (uint32_t y : p32((uint64_t)1 << 32, 300)) {
+            const uint32_t r = A::mul_u32(y, tw, md);
+            CHECK(r < 2 * (uint64_t)q && r % q == (uint32_t)(((uint64_t)w * y) % q), "Arith32 mul_u32 q=%u w=%u y=%u", q, w, y);
         }
         for (uint32_t x0 : p32(4 * q64, 60))
             for (uint32_t y0 : p32(4 * q64, 20)) {
@@ -198,6 +212,11 @@ static void check_32(uint64_t q64)
     }
     for (uint32_t x : p32(2 * q64, 40000)) CHECK(A::canon_inv(x, md) == x % q, "Arith32 canon_inv %u", x);
     for (int v = -40; v <= 40; ++v) CHECK(A::from_small(v, md) == mod_of(v, q), "Arith32 from_small %d", v);
+    for (int v = -32; v <= 32; ++v)
+        for (uint32_t x : p32(2 * q64, 50)) {
+            const uint32_t r = A::add_small(x, v, md);
+            CHECK(r % q == mod_of((i128)x + v, q) && r < 3 * q64, "Arith32 add_small %u %d", x, v);
+        }
 }
 
 // ------------------------------------------------------------------ residues in doubles
@@ -225,6 +244,11 @@ static void check_f(uint64_t q)
             const i128 exact = (i128)w64 * (i128)(long long)y;
             CHECK(r == std::floor(r) && std::fabs(r) <= prod_bound(w64, y) && mod_of((i128)(long long)r, q) == mod_of(exact, q),
                   "ArithF mul q=%llu w=%llu y=%.0f -> %.0f", (unsigned long long)q, (unsigned long long)w64, y, r);
+        }
+        for (uint64_t y : probes(1ull << 30, q, 300)) {                    // plaintext coefficients are below 2^30
+            const double r = A::mul_u32((uint32_t)y, tw, md);
+            CHECK(std::fabs(r) <= prod_bound(w64, (double)y) && mod_of((i128)(long long)r, q) == (uint64_t)(((u128)w64 * y) % q),
+                  "ArithF mul_u32 q=%llu w=%llu y=%llu", (unsigned long long)q, (unsigned long long)w64, (unsigned long long)y);
         }
         for (double x0 : signed_probes(63 * q, 40))
             for (double y0 : signed_probes(lim40, 12)) {
