@@ -120,6 +120,31 @@ D2_DEV void st64(void *base, uint32_t lane_off, uint32_t slot_off, uint64_t val)
     *(uint64_t *)((char *)base + lane_off + slot_off) = val;
 #endif
 }
+// The same load marked non-temporal (streaming): for data read exactly once.
+D2_DEV uint64_t ld64_stream(const void *base, uint32_t lane_off, uint32_t slot_off)
+{
+#if D2_GCN_ASM
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, 0xffffffff, 0x00020000);
+    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, lane_off, slot_off, 2 /* nt */);
+    return ((uint64_t)v.y << 32) | v.x;
+#else
+    return *(const uint64_t *)((const char *)base + lane_off + slot_off);
+#endif
+}
+// The same store marked non-temporal (streaming): for data the kernel never reads again, so that it
+// does not displace what the kernel does re-read (parked words, keys, twiddles) from the caches.
+D2_DEV void st64_stream(void *base, uint32_t lane_off, uint32_t slot_off, uint64_t val)
+{
+#if D2_GCN_ASM
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(base, 0, 0xffffffff, 0x00020000);
+    u32x2 v;
+    v.x = (uint32_t)val;
+    v.y = (uint32_t)(val >> 32);
+    __builtin_amdgcn_raw_buffer_store_b64(v, r, lane_off, slot_off, 2 /* nt */);
+#else
+    *(uint64_t *)((char *)base + lane_off + slot_off) = val;
+#endif
+}
 D2_DEV uint64_t const_ld64(const void *base, uint32_t byte_off)
 {
 #if D2_GCN_ASM

@@ -596,7 +596,7 @@ D2_DEV void mul_add_store(uint64_t *dst, const uint64_t *kp, const uint64_t *kps
             }
         }
 #pragma unroll
-        for (int k = 0; k < BATCH; ++k) st64(dst, lo, 8u * ENG::T * (b * BATCH + k), r[k]);
+        for (int k = 0; k < BATCH; ++k) st64_stream(dst, lo, 8u * ENG::T * (b * BATCH + k), r[k]);
     }
 }
 
@@ -792,11 +792,11 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
         constexpr bool PIPE = E <= 8 && !CONVERT;
         uint64_t y[E], hv[E];
 #pragma unroll
-        for (int k = 0; k < E; ++k) y[k] = ld64(c0 + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
+        for (int k = 0; k < E; ++k) y[k] = ld64_stream(c0 + off, 8u * (uint32_t)tl, 8u * ENG::T * k);
         if (PIPE && K > 0) {
             const uint64_t *h = share_of(0) + (size_t)c * share_ct + off;
 #pragma unroll
-            for (int k = 0; k < E; ++k) hv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
+            for (int k = 0; k < E; ++k) hv[k] = ld64_stream(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
         }
         for (uint32_t j = 0; j < K; ++j) {
             if constexpr (PIPE) {
@@ -804,7 +804,7 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
                 if (j + 1 < K) {
                     const uint64_t *h = share_of(j + 1) + (size_t)c * share_ct + off;
 #pragma unroll
-                    for (int k = 0; k < E; ++k) nv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
+                    for (int k = 0; k < E; ++k) nv[k] = ld64_stream(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
                 }
 #pragma unroll
                 for (int k = 0; k < E; ++k) {
@@ -814,7 +814,7 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
             } else {
                 const uint64_t *h = share_of(j) + (size_t)c * share_ct + off;
 #pragma unroll
-                for (int k = 0; k < E; ++k) hv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
+                for (int k = 0; k < E; ++k) hv[k] = ld64_stream(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
 #pragma unroll
                 for (int k = 0; k < E; ++k) y[k] = add_mod(y[k], hv[k], q);
             }
@@ -823,11 +823,11 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
         if constexpr (CONVERT) {
             uint64_t z[E];
 #pragma unroll
-            for (int k = 0; k < E; ++k) z[k] = keep_c1 ? ld64(c0 + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k) : 0;
+            for (int k = 0; k < E; ++k) z[k] = keep_c1 ? ld64_stream(c0 + LN + off, 8u * (uint32_t)tl, 8u * ENG::T * k) : 0;
             for (uint32_t j = 0; j < K; ++j) {
                 const uint64_t *h = share_of(j) + (size_t)c * share_ct + LN + off;
 #pragma unroll
-                for (int k = 0; k < E; ++k) hv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
+                for (int k = 0; k < E; ++k) hv[k] = ld64_stream(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
 #pragma unroll
                 for (int k = 0; k < E; ++k) z[k] = add_mod(z[k], hv[k], q);
             }
@@ -871,7 +871,7 @@ D2_DEV void combine_body(uint64_t *lds, const uint64_t *ct, SH share_of, uint32_
             for (uint32_t j = 0; j < K; ++j) {
                 const uint64_t *h = share_of(j) + (size_t)c * share_ct + LN + off;
 #pragma unroll
-                for (int k = 0; k < E; ++k) hv[k] = ld64(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
+                for (int k = 0; k < E; ++k) hv[k] = ld64_stream(h, 8u * (uint32_t)tl, 8u * ENG::T * k);
 #pragma unroll
                 for (int k = 0; k < E; ++k) y[k] = add_mod(y[k], hv[k], q);
             }

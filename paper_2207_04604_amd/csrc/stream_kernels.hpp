@@ -89,9 +89,14 @@ __global__ void __launch_bounds__(256) k_sum_groups(GroupJobs jobs, size_t strid
     const uint32_t job = gridDim.y - 1 - blockIdx.y, K = jobs.K[job];
     const uint64_t *src = jobs.first[job];
     uint64_t q = tabs[(i >> log2n) % L].q;
-    ulonglong2 acc = *(const ulonglong2 *)(src + i);
+    // streaming loads: every fresh ciphertext is read exactly once here
+    typedef unsigned long long v2u64 __attribute__((ext_vector_type(2)));
+    const v2u64 first = __builtin_nontemporal_load((const v2u64 *)(src + i));
+    ulonglong2 acc;
+    acc.x = first.x;
+    acc.y = first.y;
     for (uint32_t k = 1; k < K; ++k) {
-        ulonglong2 v = *(const ulonglong2 *)(src + (size_t)k * stride + i);
+        const v2u64 v = __builtin_nontemporal_load((const v2u64 *)(src + (size_t)k * stride + i));
         acc.x = add_mod(acc.x, v.x, q);
         acc.y = add_mod(acc.y, v.y, q);
     }
