@@ -82,7 +82,7 @@ def test_bootstrap_C2_one_group_every_coefficient():
 def test_bootstrap_wide_primes_ragged_tail_and_extreme_ids():
     from oracle import oracle as O
     from paper_2207_04604_amd.synth import toy_config
-    for bits, log2n, L in ((54, 11, 2), (60, 10, 2), (36, 13, 2)):
+    for bits, log2n, L in ((54, 11, 2), (60, 10, 2), (36, 13, 2), (54, 14, 2), (60, 14, 1), (44, 14, 1)):
         cfg = toy_config(log2n, O.find_primes(bits, log2n, L), 65537, 3, (1 << log2n) + 77, frac_bits=6)
         o, ctx, perm = make_pair(cfg)
         rng = np.random.default_rng(bits + 1)
