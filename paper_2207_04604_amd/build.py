@@ -30,3 +30,15 @@ def build_library(jobs: int = 8) -> str:
         objs = list(pool.map(_compile, sources()))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT, *objs])
     return OUT
+
+
+DEVICE_CHECK_SRC = os.path.join(os.path.dirname(HERE), "tests", "arith_device_check.hip")
+DEVICE_CHECK_EXE = os.path.join(os.path.dirname(HERE), "tests", "_build", "arith_device_check")
+
+
+def build_device_check() -> str:
+    """The GPU-side check of the arithmetic policies (tests/arith_device_check.hip): a stand-alone program."""
+    os.makedirs(os.path.dirname(DEVICE_CHECK_EXE), exist_ok=True)
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-O2", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                           "-packed-fp32-ops", "-o", DEVICE_CHECK_EXE, DEVICE_CHECK_SRC], stderr=subprocess.STDOUT)
+    return DEVICE_CHECK_EXE

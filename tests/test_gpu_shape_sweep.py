@@ -95,3 +95,17 @@ def test_transforms_of_extreme_polynomials(log2n, bits):
         natural[perm] = pats[b, 0]                 # position p of the layout holds evaluation perm[p]
         assert np.array_equal(got[b, 0], O.ntt_inverse(natural, q, o.psi[0])), f"inverse transform, pattern {b}"
     ctx.close()
+
+
+def test_arithmetic_policies_hold_their_contracts_on_the_device():
+    """tests/arith_device_check.hip: every operation of every arithmetic policy, as compiled for the GPU (the
+    inline-assembly side), on inputs at the ends of the documented ranges, against 128-bit integers."""
+    import os
+    import subprocess
+    from paper_2207_04604_amd import build
+    exe = build.DEVICE_CHECK_EXE
+    if not os.path.exists(exe):
+        build.build_device_check()
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert run.returncode == 0, run.stdout[-3000:]
+    assert "all arithmetic policies hold their contracts on the device" in run.stdout
