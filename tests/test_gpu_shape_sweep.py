@@ -19,7 +19,7 @@ pytestmark = pytest.mark.gpu
 # plaintext modulus leaves room for the noise.
 SCHEME_SHAPES = [(10, 30, 2), (10, 31, 2), (11, 30, 2), (12, 30, 2), (12, 27, 3), (14, 30, 2), (10, 44, 2), (10, 45, 1), (10, 55, 2), (10, 56, 1), (10, 61, 2), (11, 36, 3), (11, 44, 1), (11, 61, 2),
                  (12, 45, 2), (12, 55, 1), (12, 61, 2), (13, 30, 2), (13, 44, 2), (13, 56, 1), (13, 61, 2), (14, 36, 2),
-                 (14, 44, 1), (14, 61, 2)]
+                 (14, 44, 1), (14, 61, 2), (14, 45, 2), (14, 55, 1), (13, 54, 2)]
 
 
 @pytest.mark.parametrize("log2n,bits,L", SCHEME_SHAPES)
